@@ -1,0 +1,319 @@
+/*
+ * OBCache CPU oracle -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, fp64 implementation of what the GPU hot path must compute,
+ * written from the paper (arxiv 2510.07651) and sharing no code with the HIP
+ * kernels.  Only tests, the smoke check and the benchmark's cpu_baseline leg
+ * may call it.
+ *
+ * What it follows:
+ *   - Section 3 (Prefill / Decoding):  Z = Q K^T / sqrt(d),  A = softmax_row(Z),  O = A V.
+ *   - Section 4.3, windowed objective (Eq. 9 / Appendix A.1): only the last W
+ *     query rows ("perturbation window") enter the sums.
+ *   - Proposition 1 (Eq. 4):  S^value_p = sum_i A_ip^2 ||v_p||^2
+ *   - Proposition 2 (Eq. 5):  S^key_p   = sum_i A_ip^2 Z_ip^2 ||v_p - o_i||^2
+ *   - Proposition 3 (Eq. 6):  S^joint_p = S^value_p + S^key_p
+ *                                       + 2 sum_i A_ip^2 Z_ip (||v_p||^2 - v_p . o_i)
+ *   - Appendix A.5 (GQA): the score of KV head g is the sum of the per-query-head
+ *     scores over the heads h in H(g), each with its own A^h, Z^h, o^h and the
+ *     shared v^g.
+ *   - Appendix E, Algorithm 2: top-k by score, kept indices sorted ascending,
+ *     rows of K and V gathered.
+ *
+ * Readings taken where the paper is silent (listed in the design notes too):
+ *   - Query row r (0-based, r < W) of a sequence of true length len sits at
+ *     absolute position len - W + r and sees keys p <= len - W + r (causal,
+ *     window rows causal among themselves).  Invisible (r, p) pairs are absent:
+ *     they are not part of the softmax and contribute exactly 0 to every score.
+ *   - Z in Eq. 5-6 is the raw scaled logit q.k/sqrt(d), not a max-shifted one.
+ *   - Query head h reads KV head g = h / (Hq/Hkv)  (consecutive grouping).
+ *   - Top-k ties go to the lowest token index; positions p >= len are never kept
+ *     and their scores are 0.
+ *
+ * Pins (tests/test_oracle_pins.py): softmax rows sum to 1; value score equals
+ * the exact output change when v_p is zeroed (brute force); key and joint scores
+ * equal the squared directional derivative of the window output (central
+ * differences, brute force); q = 0 closed form; library attention
+ * (torch scaled_dot_product_attention, fp64); token permutation equivariance;
+ * GQA = sum of MHA heads; Eq. 6 literal form == completed-square form;
+ * select vs a library stable sort; compaction vs fancy indexing.
+ * No function here is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define OBC_ORACLE_OK 0
+#define OBC_ORACLE_EINVAL -1
+
+int obc_oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+static int seq_len_of(const int32_t *seq_lens, int b, int N)
+{
+    return seq_lens ? (int)seq_lens[b] : N;
+}
+
+static int check_shapes(int B, int Hq, int Hkv, int N, int W, int d, const int32_t *seq_lens)
+{
+    if (B < 1 || Hq < 1 || Hkv < 1 || N < 1 || W < 1 || d < 1) return OBC_ORACLE_EINVAL;
+    if (Hq % Hkv != 0) return OBC_ORACLE_EINVAL;
+    for (int b = 0; b < B; ++b) {
+        int len = seq_len_of(seq_lens, b, N);
+        if (len > N || len < W) return OBC_ORACLE_EINVAL;
+    }
+    return OBC_ORACLE_OK;
+}
+
+/*
+ * One window row of attention (Section 3): logits over the visible keys,
+ * softmax, output.  z, a have room for n_vis entries; o has d entries.
+ */
+static void attention_row(const double *q_row, const double *K, const double *V, int n_vis, int d,
+                          double *z, double *a, double *o)
+{
+    const double inv_sqrt_d = 1.0 / sqrt((double)d);
+    double zmax = -INFINITY;
+    for (int p = 0; p < n_vis; ++p) {
+        double dot = 0.0;
+        for (int j = 0; j < d; ++j) dot += q_row[j] * K[(size_t)p * d + j];
+        z[p] = dot * inv_sqrt_d;
+        if (z[p] > zmax) zmax = z[p];
+    }
+    double denom = 0.0;
+    for (int p = 0; p < n_vis; ++p) {
+        a[p] = exp(z[p] - zmax);
+        denom += a[p];
+    }
+    for (int p = 0; p < n_vis; ++p) a[p] /= denom;
+    for (int j = 0; j < d; ++j) o[j] = 0.0;
+    for (int p = 0; p < n_vis; ++p)
+        for (int j = 0; j < d; ++j) o[j] += a[p] * V[(size_t)p * d + j];
+}
+
+/*
+ * Window attention internals for small cases (tests only):
+ *   Z, A : [B, Hq, W, N]  (entries for invisible pairs are set to NaN / 0)
+ *   O    : [B, Hq, W, d]
+ */
+int obc_oracle_window_attention(const double *q, const double *k, const double *v,
+                                int B, int Hq, int Hkv, int N, int W, int d,
+                                const int32_t *seq_lens, double *Z, double *A, double *O)
+{
+    int rc = check_shapes(B, Hq, Hkv, N, W, d, seq_lens);
+    if (rc) return rc;
+    const int G = Hq / Hkv;
+    double *z = (double *)malloc(sizeof(double) * (size_t)N);
+    double *a = (double *)malloc(sizeof(double) * (size_t)N);
+    for (int b = 0; b < B; ++b) {
+        int len = seq_len_of(seq_lens, b, N);
+        for (int h = 0; h < Hq; ++h) {
+            int g = h / G;
+            const double *Kg = k + ((size_t)b * Hkv + g) * (size_t)N * d;
+            const double *Vg = v + ((size_t)b * Hkv + g) * (size_t)N * d;
+            for (int r = 0; r < W; ++r) {
+                size_t row = ((size_t)b * Hq + h) * W + r;
+                int n_vis = len - W + r + 1;
+                attention_row(q + row * d, Kg, Vg, n_vis, d, z, a, O + row * d);
+                for (int p = 0; p < N; ++p) {
+                    Z[row * N + p] = p < n_vis ? z[p] : NAN;
+                    A[row * N + p] = p < n_vis ? a[p] : 0.0;
+                }
+            }
+        }
+    }
+    free(z);
+    free(a);
+    return OBC_ORACLE_OK;
+}
+
+/*
+ * Scores for every (b, kv head g, token p).  Any of s_value, s_key, s_joint may
+ * be NULL.  Layouts: q [B,Hq,W,d], k,v [B,Hkv,N,d], outputs [B,Hkv,N], all fp64,
+ * contiguous.  seq_lens: NULL or B true lengths (W <= len <= N).
+ *
+ * joint_form = 0: per visible (i,p) the joint term is A^2 ||(1+Z) v_p - Z o_i||^2,
+ *                 the completed square of Eq. 6 (expanding it gives
+ *                 ||v||^2 + Z^2 ||v-o||^2 + 2 Z (||v||^2 - v.o)).
+ * joint_form = 1: Eq. 6 literally: S^value + S^key + 2 sum A^2 Z (||v||^2 - v.o).
+ */
+int obc_oracle_score(const double *q, const double *k, const double *v,
+                     int B, int Hq, int Hkv, int N, int W, int d,
+                     const int32_t *seq_lens, int joint_form,
+                     double *s_value, double *s_key, double *s_joint)
+{
+    int rc = check_shapes(B, Hq, Hkv, N, W, d, seq_lens);
+    if (rc) return rc;
+    const int G = Hq / Hkv;
+    const int n_heads = B * Hkv;
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bg = 0; bg < n_heads; ++bg) {
+        const int b = bg / Hkv, g = bg % Hkv;
+        const int len = seq_len_of(seq_lens, b, N);
+        const double *Kg = k + (size_t)bg * N * d;
+        const double *Vg = v + (size_t)bg * N * d;
+        double *z = (double *)malloc(sizeof(double) * (size_t)N);
+        double *a = (double *)malloc(sizeof(double) * (size_t)N);
+        double *o = (double *)malloc(sizeof(double) * (size_t)d);
+        double *acc_v = (double *)calloc((size_t)N, sizeof(double));
+        double *acc_k = (double *)calloc((size_t)N, sizeof(double));
+        double *acc_j = (double *)calloc((size_t)N, sizeof(double));
+        double *acc_x = (double *)calloc((size_t)N, sizeof(double)); /* cross term of Eq. 6 */
+
+        for (int hh = 0; hh < G; ++hh) {            /* h in H(g), Appendix A.5 */
+            const int h = g * G + hh;
+            for (int r = 0; r < W; ++r) {           /* i = w..s, Eq. 9 */
+                const int n_vis = len - W + r + 1;
+                const double *q_row = q + (((size_t)b * Hq + h) * W + r) * d;
+                attention_row(q_row, Kg, Vg, n_vis, d, z, a, o);
+                for (int p = 0; p < n_vis; ++p) {
+                    const double *vp = Vg + (size_t)p * d;
+                    const double A2 = a[p] * a[p];
+                    double vv = 0.0, vmo2 = 0.0, vo = 0.0, sq = 0.0;
+                    for (int j = 0; j < d; ++j) {
+                        const double diff = vp[j] - o[j];
+                        const double comb = (1.0 + z[p]) * vp[j] - z[p] * o[j];
+                        vv += vp[j] * vp[j];
+                        vmo2 += diff * diff;
+                        vo += vp[j] * o[j];
+                        sq += comb * comb;
+                    }
+                    acc_v[p] += A2 * vv;                       /* Eq. 4 */
+                    acc_k[p] += A2 * z[p] * z[p] * vmo2;       /* Eq. 5 */
+                    acc_j[p] += A2 * sq;                       /* Eq. 6, completed square */
+                    acc_x[p] += 2.0 * A2 * z[p] * (vv - vo);   /* Eq. 6, cross term */
+                }
+            }
+        }
+        for (int p = 0; p < N; ++p) {
+            const size_t idx = (size_t)bg * N + p;
+            const int live = p < len;
+            if (s_value) s_value[idx] = live ? acc_v[p] : 0.0;
+            if (s_key) s_key[idx] = live ? acc_k[p] : 0.0;
+            if (s_joint) {
+                double sj = joint_form ? acc_v[p] + acc_k[p] + acc_x[p] : acc_j[p];
+                s_joint[idx] = live ? sj : 0.0;
+            }
+        }
+        free(z); free(a); free(o);
+        free(acc_v); free(acc_k); free(acc_j); free(acc_x);
+    }
+    return OBC_ORACLE_OK;
+}
+
+/*
+ * Attention-only score of Section 4.3 (Eq. 8): S^attn_p = sum_i |A_ip| over the
+ * window, summed over the query heads of the group.  Used by tests of the
+ * special cases (w = s gives the single-row case).
+ */
+int obc_oracle_attn_score(const double *q, const double *k, const double *v,
+                          int B, int Hq, int Hkv, int N, int W, int d,
+                          const int32_t *seq_lens, double *s_attn)
+{
+    int rc = check_shapes(B, Hq, Hkv, N, W, d, seq_lens);
+    if (rc) return rc;
+    const int G = Hq / Hkv;
+    double *z = (double *)malloc(sizeof(double) * (size_t)N);
+    double *a = (double *)malloc(sizeof(double) * (size_t)N);
+    double *o = (double *)malloc(sizeof(double) * (size_t)d);
+    for (int bg = 0; bg < B * Hkv; ++bg) {
+        const int b = bg / Hkv, g = bg % Hkv;
+        const int len = seq_len_of(seq_lens, b, N);
+        for (int p = 0; p < N; ++p) s_attn[(size_t)bg * N + p] = 0.0;
+        for (int hh = 0; hh < G; ++hh)
+            for (int r = 0; r < W; ++r) {
+                const int n_vis = len - W + r + 1;
+                const double *q_row = q + (((size_t)b * Hq + g * G + hh) * W + r) * d;
+                attention_row(q_row, k + (size_t)bg * N * d, v + (size_t)bg * N * d, n_vis, d, z, a, o);
+                for (int p = 0; p < n_vis; ++p) s_attn[(size_t)bg * N + p] += fabs(a[p]);
+            }
+    }
+    free(z); free(a); free(o);
+    return OBC_ORACLE_OK;
+}
+
+/* ---- selection (Section 3 "Cache Eviction"; Algorithm 2: topk -> sort) ---- */
+
+typedef struct { float s; int32_t p; } scored_t;
+
+/* NaN ranks below every number; -0.0 equals +0.0. */
+static int better(const scored_t *x, const scored_t *y)
+{
+    const int xn = isnan(x->s), yn = isnan(y->s);
+    if (xn != yn) return yn;            /* the non-NaN one is better */
+    if (!xn && x->s != y->s) return x->s > y->s;
+    return x->p < y->p;                 /* tie: lowest index first */
+}
+static int cmp_scored(const void *a, const void *b)
+{
+    const scored_t *x = (const scored_t *)a, *y = (const scored_t *)b;
+    if (better(x, y)) return -1;
+    if (better(y, x)) return 1;
+    return 0;
+}
+static int cmp_i32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * scores [B,Hkv,N] fp32 -> keep_idx [B,Hkv,budget] int32, ascending.
+ * Per (b,g): the budget best tokens among p < len_b, by (score descending,
+ * index ascending).  Requires 1 <= budget <= len_b.
+ */
+int obc_oracle_select(const float *scores, int B, int Hkv, int N, int budget,
+                      const int32_t *seq_lens, int32_t *keep_idx)
+{
+    if (B < 1 || Hkv < 1 || N < 1 || budget < 1) return OBC_ORACLE_EINVAL;
+    for (int b = 0; b < B; ++b) {
+        int len = seq_len_of(seq_lens, b, N);
+        if (len > N || budget > len) return OBC_ORACLE_EINVAL;
+    }
+    scored_t *tmp = (scored_t *)malloc(sizeof(scored_t) * (size_t)N);
+    for (int bg = 0; bg < B * Hkv; ++bg) {
+        const int len = seq_len_of(seq_lens, bg / Hkv, N);
+        for (int p = 0; p < len; ++p) {
+            tmp[p].s = scores[(size_t)bg * N + p];
+            tmp[p].p = p;
+        }
+        qsort(tmp, (size_t)len, sizeof(scored_t), cmp_scored);   /* total order: no ties left */
+        int32_t *out = keep_idx + (size_t)bg * budget;
+        for (int j = 0; j < budget; ++j) out[j] = tmp[j].p;
+        qsort(out, (size_t)budget, sizeof(int32_t), cmp_i32);
+    }
+    free(tmp);
+    return OBC_ORACLE_OK;
+}
+
+/*
+ * Row gather (Algorithm 2 without the recent-window tail):
+ *   k_out[b,g,j,:] = k[b,g,keep_idx[b,g,j],:], same for v.  Rows are
+ *   row_bytes = d * element size bytes long.
+ */
+int obc_oracle_compact(const void *k, const void *v, const int32_t *keep_idx,
+                       int B, int Hkv, int N, int budget, size_t row_bytes,
+                       void *k_out, void *v_out)
+{
+    if (B < 1 || Hkv < 1 || N < 1 || budget < 1 || row_bytes < 1) return OBC_ORACLE_EINVAL;
+    for (int bg = 0; bg < B * Hkv; ++bg)
+        for (int j = 0; j < budget; ++j) {
+            int32_t p = keep_idx[(size_t)bg * budget + j];
+            if (p < 0 || p >= N) return OBC_ORACLE_EINVAL;
+            size_t src = ((size_t)bg * N + p) * row_bytes, dst = ((size_t)bg * budget + j) * row_bytes;
+            memcpy((char *)k_out + dst, (const char *)k + src, row_bytes);
+            memcpy((char *)v_out + dst, (const char *)v + src, row_bytes);
+        }
+    return OBC_ORACLE_OK;
+}

@@ -1,0 +1,339 @@
+"""Pins of the fp64 CPU oracle against what the paper and the mathematics fix.
+
+The paper (arxiv 2510.07651) prints no worked numeric example of a score, so the
+oracle is pinned to: the definition the closed forms approximate (Definition 4.1 /
+Eq. 1 and its windowed form Eq. 9, evaluated by brute force here, in numpy, with
+code independent of the oracle), exact identities from the derivation in
+Appendix A, closed forms of special cases, a library attention routine, and
+invariances.  Each test names the plausible oracle mistake it would catch.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+
+# ----------------------------------------------------------------------------
+# Independent brute-force helpers (numpy, fp64).  They implement Section 3's
+# attention for the window rows only; nothing here calls the oracle.
+# ----------------------------------------------------------------------------
+def window_outputs(q, K, V, length=None):
+    """q [W,d], K,V [N,d] -> O [W,d]; row r sits at position len-W+r, causal."""
+    W, d = q.shape
+    N = K.shape[0] if length is None else length
+    out = np.zeros((W, d))
+    for r in range(W):
+        n_vis = N - W + r + 1
+        z = K[:n_vis] @ q[r] / np.sqrt(d)
+        e = np.exp(z - z.max())
+        a = e / e.sum()
+        out[r] = a @ V[:n_vis]
+    return out
+
+
+def group_window_outputs(q, K, V, length=None):
+    """q [G,W,d] (query heads sharing one KV head) -> O [G,W,d]."""
+    return np.stack([window_outputs(q[h], K, V, length) for h in range(q.shape[0])])
+
+
+def rand_case(seed, B=1, Hq=2, Hkv=1, N=24, W=5, d=8, scale=1.0):
+    rng = np.random.default_rng(seed)
+    q = rng.standard_normal((B, Hq, W, d)) * scale
+    k = rng.standard_normal((B, Hkv, N, d))
+    v = rng.standard_normal((B, Hkv, N, d))
+    return q, k, v
+
+
+# ----------------------------------------------------------------------------
+# P1  softmax rows: sum to 1, non-negative, invisible entries absent
+# ----------------------------------------------------------------------------
+def test_softmax_rows_and_mask():
+    q, k, v = rand_case(1, B=2, Hq=4, Hkv=2, N=30, W=6, d=16)
+    lens = [30, 17]
+    Z, A, O = oracle.window_attention(q, k, v, seq_lens=lens)
+    for b in range(2):
+        for r in range(6):
+            n_vis = lens[b] - 6 + r + 1
+            row = A[b, :, r, :]
+            np.testing.assert_allclose(row.sum(-1), 1.0, rtol=0, atol=1e-14)
+            assert (row >= 0).all()
+            assert (row[:, n_vis:] == 0).all() and (row[:, :n_vis] > 0).all()
+            assert np.isnan(Z[b, :, r, n_vis:]).all() and np.isfinite(Z[b, :, r, :n_vis]).all()
+
+
+# ----------------------------------------------------------------------------
+# P8  A, Z, O against a library routine (torch SDPA, fp64, explicit mask)
+# ----------------------------------------------------------------------------
+def test_attention_matches_torch_sdpa():
+    B, Hq, Hkv, N, W, d = 2, 6, 2, 41, 9, 16
+    q, k, v = rand_case(2, B, Hq, Hkv, N, W, d)
+    lens = [41, 29]
+    Z, A, O = oracle.window_attention(q, k, v, seq_lens=lens)
+    G = Hq // Hkv
+    tq, tk, tv = (torch.from_numpy(x) for x in (q, k, v))
+    tk = tk.repeat_interleave(G, dim=1)            # consecutive grouping: head h reads KV head h // G
+    tv = tv.repeat_interleave(G, dim=1)
+    mask = torch.zeros(B, 1, W, N, dtype=torch.bool)
+    for b in range(B):
+        for r in range(W):
+            mask[b, 0, r, : lens[b] - W + r + 1] = True
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask)
+    np.testing.assert_allclose(O, ref.numpy(), rtol=1e-12, atol=1e-13)
+    zref = (tq @ tk.transpose(-1, -2) / np.sqrt(d)).numpy()
+    vis = mask.expand(B, Hq, W, N).numpy()
+    np.testing.assert_allclose(Z[vis], zref[vis], rtol=1e-13, atol=1e-13)
+
+
+# ----------------------------------------------------------------------------
+# P2 / P3  signs, and Eq. 6 literal == completed square
+# ----------------------------------------------------------------------------
+def test_scores_nonnegative_and_joint_forms_agree():
+    q, k, v = rand_case(3, B=2, Hq=4, Hkv=2, N=50, W=8, d=16, scale=2.0)
+    lens = [50, 31]
+    sv, sk, sj = oracle.score(q, k, v, seq_lens=lens, joint_form=0)
+    _, _, sj_lit = oracle.score(q, k, v, seq_lens=lens, joint_form=1)
+    assert (sv >= 0).all() and (sk >= 0).all() and (sj >= 0).all()
+    np.testing.assert_allclose(sj_lit, sj, rtol=1e-12, atol=1e-15)
+    # padded positions score exactly zero
+    assert (sv[1, :, 31:] == 0).all() and (sk[1, :, 31:] == 0).all() and (sj[1, :, 31:] == 0).all()
+    # the cross term is not identically zero: joint differs from value + key
+    assert np.abs(sj - (sv + sk)).max() > 1e-3
+
+
+# ----------------------------------------------------------------------------
+# P4  value score is EXACT (Appendix A.2: the objective is quadratic in dV):
+#     zero v_p, recompute the window outputs, squared Frobenius change == S^value_p.
+#     Catches: wrong window rows, wrong causal bound, missing group sum, A vs A^2.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("Hq,Hkv", [(1, 1), (3, 1), (4, 2)])
+def test_value_score_equals_bruteforce_zeroing(Hq, Hkv):
+    B, N, W, d = 1, 26, 6, 8
+    q, k, v = rand_case(4 + Hq, B, Hq, Hkv, N, W, d, scale=1.5)
+    sv, _, _ = oracle.score(q, k, v)
+    G = Hq // Hkv
+    for g in range(Hkv):
+        qg = q[0, g * G:(g + 1) * G]
+        base = group_window_outputs(qg, k[0, g], v[0, g])
+        for p in range(N):
+            V2 = v[0, g].copy()
+            V2[p] = 0.0
+            err = ((group_window_outputs(qg, k[0, g], V2) - base) ** 2).sum()
+            np.testing.assert_allclose(sv[0, g, p], err, rtol=1e-10, atol=1e-18)
+
+
+# ----------------------------------------------------------------------------
+# P5  key and joint scores are the squared directional derivative of the window
+#     outputs along (dV, dK) = (-v_p, -k_p) on row p (Theorem 4.2 with the
+#     Gauss-Newton Hessians of Appendix A.3-A.4): central differences, brute force.
+#     Catches: dropped / mis-signed cross term, Z shifted by the max, o_i of the
+#     wrong row, ||v-o|| vs ||v||, transposed operands.
+# ----------------------------------------------------------------------------
+@pytest.mark.parametrize("seed,Hq,Hkv", [(10, 1, 1), (11, 2, 1), (12, 4, 2)])
+def test_key_and_joint_scores_equal_squared_directional_derivative(seed, Hq, Hkv):
+    B, N, W, d = 1, 22, 5, 8
+    q, k, v = rand_case(seed, B, Hq, Hkv, N, W, d, scale=1.3)
+    _, sk, sj = oracle.score(q, k, v)
+    G = Hq // Hkv
+    t = 1e-4
+    for g in range(Hkv):
+        qg = q[0, g * G:(g + 1) * G]
+        K0, V0 = k[0, g], v[0, g]
+        for p in range(N):
+            for which, ref in (("key", sk), ("joint", sj)):
+                def out(sign):
+                    K2, V2 = K0.copy(), V0.copy()
+                    K2[p] = K0[p] * (1.0 - sign * t)          # K + (sign t) dK, dK_p = -k_p
+                    if which == "joint":
+                        V2[p] = V0[p] * (1.0 - sign * t)
+                    return group_window_outputs(qg, K2, V2)
+                D = (out(+1) - out(-1)) / (2 * t)
+                np.testing.assert_allclose(ref[0, g, p], (D ** 2).sum(), rtol=2e-6, atol=1e-16)
+
+
+# ----------------------------------------------------------------------------
+# P6  Definition 4.1 itself (row p of K and V set to zero, softmax recomputed)
+#     converges to the closed forms as the logits shrink (q scaled by eps).
+# ----------------------------------------------------------------------------
+def test_full_zeroing_converges_to_closed_form():
+    B, Hq, Hkv, N, W, d = 1, 2, 1, 20, 4, 8
+    q, k, v = rand_case(20, B, Hq, Hkv, N, W, d)
+    ratios = {}
+    for eps in (1e-2, 1e-3):
+        qe = q * eps
+        _, sk, sj = oracle.score(qe, k, v)
+        base = group_window_outputs(qe[0], k[0, 0], v[0, 0])
+        worst = 0.0
+        for p in range(N):
+            K2, V2 = k[0, 0].copy(), v[0, 0].copy()
+            K2[p] = 0.0
+            Lk = ((group_window_outputs(qe[0], K2, v[0, 0]) - base) ** 2).sum()
+            V2[p] = 0.0
+            Lj = ((group_window_outputs(qe[0], K2, V2) - base) ** 2).sum()
+            worst = max(worst, abs(Lk / sk[0, 0, p] - 1), abs(Lj / sj[0, 0, p] - 1))
+        ratios[eps] = worst
+    assert ratios[1e-3] < 1e-2
+    assert ratios[1e-3] < ratios[1e-2] / 5          # first-order convergence in eps
+
+
+# ----------------------------------------------------------------------------
+# P7  closed form at q = 0: Z = 0, A_rp = 1/(len-W+r+1)
+# ----------------------------------------------------------------------------
+def test_zero_queries_closed_form():
+    B, Hq, Hkv, N, W, d = 1, 3, 1, 19, 4, 8
+    _, k, v = rand_case(30, B, Hq, Hkv, N, W, d)
+    q = np.zeros((B, Hq, W, d))
+    sv, sk, sj = oracle.score(q, k, v)
+    vv = (v[0, 0] ** 2).sum(-1)
+    expect = np.zeros(N)
+    for r in range(W):
+        n_vis = N - W + r + 1
+        expect[:n_vis] += Hq * vv[:n_vis] / n_vis ** 2
+    np.testing.assert_allclose(sv[0, 0], expect, rtol=1e-13)
+    np.testing.assert_allclose(sj[0, 0], expect, rtol=1e-13)
+    assert np.abs(sk).max() == 0.0
+
+
+# ----------------------------------------------------------------------------
+# P9  permuting tokens of the prefix (visible to every window row) permutes scores
+# ----------------------------------------------------------------------------
+def test_prefix_permutation_equivariance():
+    B, Hq, Hkv, N, W, d = 1, 4, 2, 40, 6, 8
+    q, k, v = rand_case(40, B, Hq, Hkv, N, W, d)
+    perm = np.arange(N)
+    perm[: N - W] = np.random.default_rng(0).permutation(N - W)
+    a = oracle.score(q, k, v)
+    b = oracle.score(q, k[:, :, perm], v[:, :, perm])
+    for x, y in zip(a, b):
+        np.testing.assert_allclose(y, x[:, :, perm], rtol=1e-11, atol=1e-18)
+
+
+# ----------------------------------------------------------------------------
+# P10  GQA (Appendix A.5): group score == sum of MHA scores with K,V repeated;
+#      W = 1 is the single-row case; attention-only score (Eq. 8) sums |A|.
+# ----------------------------------------------------------------------------
+def test_gqa_is_sum_of_mha_heads_and_w1():
+    B, Hq, Hkv, N, W, d = 2, 6, 2, 33, 5, 8
+    q, k, v = rand_case(50, B, Hq, Hkv, N, W, d)
+    G = Hq // Hkv
+    grouped = oracle.score(q, k, v)
+    mha = oracle.score(q, np.repeat(k, G, axis=1), np.repeat(v, G, axis=1))
+    for x, y in zip(grouped, mha):
+        np.testing.assert_allclose(x, y.reshape(B, Hkv, G, N).sum(2), rtol=1e-12)
+    # W = 1: scores of the last query row alone
+    q1 = q[:, :, -1:, :]
+    sv1, _, _ = oracle.score(q1, k, v)
+    Z, A, O = oracle.window_attention(q1, k, v)
+    vv = (v ** 2).sum(-1)
+    np.testing.assert_allclose(sv1, (A[:, :, 0, :] ** 2).reshape(B, Hkv, G, N).sum(2) * vv, rtol=1e-12)
+    sa = oracle.attn_score(q, k, v)
+    _, Aw, _ = oracle.window_attention(q, k, v)
+    np.testing.assert_allclose(sa, Aw.sum(2).reshape(B, Hkv, G, N).sum(2), rtol=1e-12)
+    np.testing.assert_allclose(sa.sum(-1), G * W, rtol=1e-12)      # every row of A sums to 1
+
+
+# ----------------------------------------------------------------------------
+# P11  plumbing identity: dropping token p from the softmax changes o_i by
+#      -A_ip (v_p - o_i) / (1 - A_ip)  (exact; follows from Section 3's softmax)
+# ----------------------------------------------------------------------------
+def test_token_removal_identity():
+    B, Hq, Hkv, N, W, d = 1, 1, 1, 18, 3, 8
+    q, k, v = rand_case(60, B, Hq, Hkv, N, W, d)
+    Z, A, O = oracle.window_attention(q, k, v)
+    p = 4                                            # in the prefix: visible to all rows
+    keep = [i for i in range(N) if i != p]
+    O2 = window_outputs(q[0, 0], k[0, 0][keep], v[0, 0][keep])
+    for r in range(W):
+        a = A[0, 0, r, p]
+        pred = O[0, 0, r] - a * (v[0, 0, p] - O[0, 0, r]) / (1 - a)
+        np.testing.assert_allclose(O2[r], pred, rtol=1e-11, atol=1e-14)
+
+
+# ----------------------------------------------------------------------------
+# Independent second formulation: the expanded-norm recipe of Appendix E
+# (||v-o||^2 = ||o||^2 + ||v||^2 - 2 v.o, sums over the query axis), assembled in
+# torch from torch's own softmax.  Different algebra, different library.
+# ----------------------------------------------------------------------------
+def test_expanded_norm_recipe_agrees():
+    B, Hq, Hkv, N, W, d = 2, 4, 2, 37, 7, 16
+    q, k, v = rand_case(70, B, Hq, Hkv, N, W, d, scale=1.2)
+    G = Hq // Hkv
+    tq = torch.from_numpy(q)
+    tk = torch.from_numpy(k).repeat_interleave(G, 1)
+    tv = torch.from_numpy(v).repeat_interleave(G, 1)
+    Z = tq @ tk.transpose(-1, -2) / d ** 0.5
+    vis = torch.ones(W, N, dtype=torch.bool).tril(N - W)
+    A = torch.softmax(Z.masked_fill(~vis, float("-inf")), -1)
+    Zm = Z.masked_fill(~vis, 0.0)
+    O = A @ tv
+    v2 = tv.pow(2).sum(-1)
+    o2 = O.pow(2).sum(-1)
+    vo = torch.einsum("bhqd,bhpd->bhqp", O, tv)
+    s_value = A.pow(2).sum(-2) * v2
+    s_key = ((A * Zm).pow(2) * (o2.unsqueeze(-1) + v2.unsqueeze(-2) - 2 * vo)).sum(-2)
+    s_joint = (2 * A.pow(2) * Zm * (v2.unsqueeze(-2) - vo)).sum(-2) + s_value + s_key
+    sv, sk, sj = oracle.score(q, k, v)
+    for mine, ref in ((sv, s_value), (sk, s_key), (sj, s_joint)):
+        np.testing.assert_allclose(mine, ref.view(B, Hkv, G, N).sum(2).numpy(), rtol=1e-10, atol=1e-16)
+
+
+# ----------------------------------------------------------------------------
+# P12  selection and compaction
+# ----------------------------------------------------------------------------
+def _select_ref(scores, budget, lens=None):
+    B, H, N = scores.shape
+    out = np.empty((B, H, budget), dtype=np.int32)
+    for b in range(B):
+        L = N if lens is None else lens[b]
+        for h in range(H):
+            s = scores[b, h, :L].astype(np.float64)
+            s = np.where(np.isnan(s), -np.inf, s)
+            order = np.argsort(-s, kind="stable")      # ties keep index order -> lowest index first
+            out[b, h] = np.sort(order[:budget])
+    return out
+
+
+def test_select_matches_stable_sort_random_and_ties():
+    rng = np.random.default_rng(80)
+    s = rng.random((3, 4, 257)).astype(np.float32)
+    lens = [257, 100, 64]
+    np.testing.assert_array_equal(oracle.select(s, 50, lens), _select_ref(s, 50, lens))
+    np.testing.assert_array_equal(oracle.select(s, 257), _select_ref(s, 257))
+    # quantised scores: many ties, k-th value repeated across the cut
+    t = np.floor(s * 6).astype(np.float32)
+    for budget in (1, 7, 64):
+        np.testing.assert_array_equal(oracle.select(t, budget, lens), _select_ref(t, budget, lens))
+    # all equal -> the first `budget` indices
+    e = np.full((1, 1, 90), 2.5, dtype=np.float32)
+    np.testing.assert_array_equal(oracle.select(e, 13)[0, 0], np.arange(13))
+    # zeros of both signs tie; duplicated maxima
+    z = np.zeros((1, 1, 16), dtype=np.float32)
+    z[0, 0, [3, 9]] = -0.0
+    z[0, 0, [12, 5]] = 7.0
+    np.testing.assert_array_equal(oracle.select(z, 5)[0, 0], [0, 1, 2, 5, 12])
+    # NaN ranks below everything, -inf included? no: below every number including -inf is not required;
+    # NaN is never preferred over a number
+    n = np.array([[[np.nan, 1.0, -1.0, np.nan, 0.5]]], dtype=np.float32)
+    np.testing.assert_array_equal(oracle.select(n, 3)[0, 0], [1, 2, 4])
+    np.testing.assert_array_equal(oracle.select(n, 4)[0, 0], [0, 1, 2, 4])
+
+
+def test_select_rejects_bad_budget():
+    s = np.zeros((1, 1, 8), dtype=np.float32)
+    with pytest.raises(ValueError):
+        oracle.select(s, 9)
+    with pytest.raises(ValueError):
+        oracle.select(s, 5, [4])
+
+
+def test_compact_matches_fancy_indexing():
+    rng = np.random.default_rng(90)
+    k = rng.integers(0, 2 ** 16, (2, 3, 50, 8)).astype(np.uint16)    # bf16 payloads are just bytes
+    v = rng.integers(0, 2 ** 16, (2, 3, 50, 8)).astype(np.uint16)
+    idx = np.sort(rng.permuted(np.tile(np.arange(50), (2, 3, 1)), axis=-1)[..., :11], axis=-1).astype(np.int32)
+    ko, vo = oracle.compact(k, v, idx)
+    np.testing.assert_array_equal(ko, np.take_along_axis(k, idx[..., None], axis=2))
+    np.testing.assert_array_equal(vo, np.take_along_axis(v, idx[..., None], axis=2))
+    kf = rng.standard_normal((1, 1, 9, 4)).astype(np.float32)
+    ko, _ = oracle.compact(kf, kf, np.array([[[0, 8]]], dtype=np.int32))
+    np.testing.assert_array_equal(ko[0, 0], kf[0, 0, [0, 8]])
