@@ -1,0 +1,130 @@
+/*
+ * obcache.h -- C ABI of the MI355X (gfx950) OBCache hot path.
+ *
+ * Implements, for one attention layer, the data-parallel part of
+ * "OBCache: Optimal Brain KV Cache Pruning" (arxiv 2510.07651):
+ *
+ *   obc_score   window attention of the last W queries against all cached keys
+ *               (Section 3: Z = QK^T/sqrt(d), A = softmax(Z), O = AV), then the
+ *               closed-form saliency scores of Propositions 1-3 (Eq. 4-6) summed
+ *               over the perturbation window (Eq. 9) and over the query heads of
+ *               each KV head (Appendix A.5);
+ *   obc_select  per (sequence, KV head) top-`budget` tokens by score, kept
+ *               indices in ascending order (Section 3 "Cache Eviction";
+ *               Appendix E, Algorithm 2: topk then sort);
+ *   obc_compact gather of the surviving K and V rows (Algorithm 2: gather).
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller unless its name
+ *     ends in `_host`.  Tensors are contiguous, row-major, in the stated shape.
+ *   - Nothing here allocates, frees or synchronises.  All work is enqueued on
+ *     `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *     Outputs are valid once that stream has reached the end of the call's work.
+ *   - `seq_lens_host` is a HOST array of B true lengths (W <= len_b <= N, at
+ *     most OBC_MAX_RAGGED_BATCH entries) read before the call returns, or NULL
+ *     when every sequence has length N.  The W window queries of sequence b sit
+ *     at absolute positions len_b-W .. len_b-1; query row r sees keys
+ *     p <= len_b-W+r.  Rows p >= len_b of k and v are never interpreted (they may
+ *     hold anything, NaN included).
+ *   - Query head h reads KV head h / (Hq/Hkv).
+ *   - Return value: OBC_OK or a negative obc_status_t.  Argument errors are
+ *     detected on the host before anything is launched.
+ *   - Same inputs give bit-identical outputs (no floating-point atomics).
+ *   - The library targets gfx950 only and has no CPU fallback.
+ */
+#ifndef OBCACHE_H_
+#define OBCACHE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    OBC_OK = 0,
+    OBC_EINVAL = -1,        /* null pointer, non-positive size, Hq % Hkv != 0, W > len, budget > len ... */
+    OBC_EUNSUPPORTED = -2,  /* head_dim / dtype / window / batch outside what the kernels are built for */
+    OBC_EWORKSPACE = -3,    /* workspace missing, misaligned (256 B) or too small */
+    OBC_ELAUNCH = -4        /* the HIP runtime reported an error when enqueuing */
+} obc_status_t;
+
+typedef enum {
+    OBC_VALUE = 0,  /* Eq. 4: sum_i A_ip^2 ||v_p||^2 */
+    OBC_KEY = 1,    /* Eq. 5: sum_i A_ip^2 Z_ip^2 ||v_p - o_i||^2 */
+    OBC_JOINT = 2,  /* Eq. 6: value + key + 2 sum_i A_ip^2 Z_ip (||v_p||^2 - v_p.o_i) */
+    OBC_ALL = 3     /* all three; scores is [3][B][Hkv][N] in the order value, key, joint */
+} obc_variant_t;
+
+typedef enum {
+    OBC_F32 = 0,   /* q,k,v fp32; head_dim 64 or 128; fp32 arithmetic */
+    OBC_BF16 = 1   /* q,k,v bf16; head_dim 128 on the matrix-core path (64 on the plain path); fp32 accumulation */
+} obc_dtype_t;
+
+#define OBC_MAX_RAGGED_BATCH 128  /* largest B accepted together with seq_lens_host */
+#define OBC_MAX_WINDOW 64         /* largest W */
+#define OBC_MAX_GROUP_ROWS 512    /* largest (Hq/Hkv) * W */
+
+/*
+ * Bytes of device workspace obc_score needs for these sizes (Section 3's O and
+ * softmax statistics of the window rows, plus split-sequence partial results).
+ * *bytes_out is a multiple of 256.  Host-only; returns OBC_EINVAL /
+ * OBC_EUNSUPPORTED like obc_score would for the same sizes.
+ */
+int obc_score_workspace_bytes(int B, int N, int W, int Hq, int Hkv, int d,
+                              int dtype, int variant, size_t *bytes_out);
+
+/*
+ * Saliency scores (Propositions 1-3 / Eq. 4-6, windowed per Eq. 9, GQA-summed per
+ * Appendix A.5).
+ *   q        [B, Hq, W, d]   the last W query rows of every sequence
+ *   k, v     [B, Hkv, N, d]  the KV cache (N = padded length)
+ *   scores   [B, Hkv, N] fp32 (or [3, B, Hkv, N] for OBC_ALL), written in full:
+ *            positions p >= len_b get 0.  Must not alias the inputs.
+ *   workspace  >= obc_score_workspace_bytes(...) bytes, 256-byte aligned; its
+ *            contents are scratch (overwritten, no state carried between calls).
+ * Z in Eq. 5-6 is the raw scaled logit q.k/sqrt(d).  (query, key) pairs hidden by
+ * the causal mask contribute exactly 0.  NaN/Inf inside the first len_b rows give
+ * undefined scores.
+ */
+int obc_score(const void *q, const void *k, const void *v,
+              int N, int W, int Hq, int Hkv, int d, int variant, float *scores,
+              int B, int dtype, const int32_t *seq_lens_host,
+              void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Top-`budget` selection per (b, KV head) (Section 3 "Cache Eviction";
+ * Algorithm 2).
+ *   scores    [B, Hkv, N] fp32
+ *   keep_idx  [B, Hkv, budget] int32, ascending token indices of the `budget`
+ *             highest scores among p < len_b; equal scores are won by the lower
+ *             index; -0.0 equals +0.0; NaN ranks below every number.
+ * Requires 1 <= budget <= len_b for every b.  Needs no workspace.
+ */
+int obc_select(const float *scores, int budget, int32_t *keep_idx,
+               int B, int Hkv, int N, const int32_t *seq_lens_host, void *hip_stream);
+
+/*
+ * Compaction (Algorithm 2's gather, without the recent-window tail):
+ *   k_out[b,g,j,:] = k[b,g,keep_idx[b,g,j],:]   and the same for v.
+ *   k, v          [B, Hkv, N, d] of `dtype`
+ *   keep_idx      [B, Hkv, budget] int32, every entry in [0, N)  (device; not
+ *                 checked on the host -- entries outside [0, N) are clamped)
+ *   k_out, v_out  [B, Hkv, budget, d]; must not overlap k, v.
+ * d * element size must be a multiple of 16 bytes.
+ */
+int obc_compact(const void *k, const void *v, const int32_t *keep_idx,
+                void *k_out, void *v_out,
+                int B, int Hkv, int N, int budget, int d, int dtype, void *hip_stream);
+
+/* Static, human-readable name of a status code. */
+const char *obc_status_string(int status);
+
+/* Library ABI version (major * 100 + minor). */
+int obc_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OBCACHE_H_ */

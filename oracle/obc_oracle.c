@@ -155,60 +155,69 @@ int obc_oracle_score(const double *q, const double *k, const double *v,
     int rc = check_shapes(B, Hq, Hkv, N, W, d, seq_lens);
     if (rc) return rc;
     const int G = Hq / Hkv;
-    const int n_heads = B * Hkv;
+    const int n_qheads = B * Hq;
+
+    /* Per-query-head scores S_{p,h} (Appendix A.5, first display), one slab per (b, h). */
+    double *hv = (double *)calloc((size_t)n_qheads * N, sizeof(double));
+    double *hk = (double *)calloc((size_t)n_qheads * N, sizeof(double));
+    double *hj = (double *)calloc((size_t)n_qheads * N, sizeof(double));
+    double *hx = (double *)calloc((size_t)n_qheads * N, sizeof(double)); /* cross term of Eq. 6 */
+    if (!hv || !hk || !hj || !hx) { free(hv); free(hk); free(hj); free(hx); return OBC_ORACLE_EINVAL; }
 
 #pragma omp parallel for schedule(dynamic, 1)
-    for (int bg = 0; bg < n_heads; ++bg) {
-        const int b = bg / Hkv, g = bg % Hkv;
+    for (int bh = 0; bh < n_qheads; ++bh) {
+        const int b = bh / Hq, h = bh % Hq, g = h / G;
         const int len = seq_len_of(seq_lens, b, N);
-        const double *Kg = k + (size_t)bg * N * d;
-        const double *Vg = v + (size_t)bg * N * d;
+        const double *Kg = k + ((size_t)b * Hkv + g) * (size_t)N * d;
+        const double *Vg = v + ((size_t)b * Hkv + g) * (size_t)N * d;
         double *z = (double *)malloc(sizeof(double) * (size_t)N);
         double *a = (double *)malloc(sizeof(double) * (size_t)N);
         double *o = (double *)malloc(sizeof(double) * (size_t)d);
-        double *acc_v = (double *)calloc((size_t)N, sizeof(double));
-        double *acc_k = (double *)calloc((size_t)N, sizeof(double));
-        double *acc_j = (double *)calloc((size_t)N, sizeof(double));
-        double *acc_x = (double *)calloc((size_t)N, sizeof(double)); /* cross term of Eq. 6 */
-
-        for (int hh = 0; hh < G; ++hh) {            /* h in H(g), Appendix A.5 */
-            const int h = g * G + hh;
-            for (int r = 0; r < W; ++r) {           /* i = w..s, Eq. 9 */
-                const int n_vis = len - W + r + 1;
-                const double *q_row = q + (((size_t)b * Hq + h) * W + r) * d;
-                attention_row(q_row, Kg, Vg, n_vis, d, z, a, o);
-                for (int p = 0; p < n_vis; ++p) {
-                    const double *vp = Vg + (size_t)p * d;
-                    const double A2 = a[p] * a[p];
-                    double vv = 0.0, vmo2 = 0.0, vo = 0.0, sq = 0.0;
-                    for (int j = 0; j < d; ++j) {
-                        const double diff = vp[j] - o[j];
-                        const double comb = (1.0 + z[p]) * vp[j] - z[p] * o[j];
-                        vv += vp[j] * vp[j];
-                        vmo2 += diff * diff;
-                        vo += vp[j] * o[j];
-                        sq += comb * comb;
-                    }
-                    acc_v[p] += A2 * vv;                       /* Eq. 4 */
-                    acc_k[p] += A2 * z[p] * z[p] * vmo2;       /* Eq. 5 */
-                    acc_j[p] += A2 * sq;                       /* Eq. 6, completed square */
-                    acc_x[p] += 2.0 * A2 * z[p] * (vv - vo);   /* Eq. 6, cross term */
+        double *acc_v = hv + (size_t)bh * N, *acc_k = hk + (size_t)bh * N;
+        double *acc_j = hj + (size_t)bh * N, *acc_x = hx + (size_t)bh * N;
+        for (int r = 0; r < W; ++r) {               /* i = w..s, Eq. 9 */
+            const int n_vis = len - W + r + 1;
+            const double *q_row = q + ((size_t)bh * W + r) * d;
+            attention_row(q_row, Kg, Vg, n_vis, d, z, a, o);
+            for (int p = 0; p < n_vis; ++p) {
+                const double *vp = Vg + (size_t)p * d;
+                const double A2 = a[p] * a[p];
+                double vv = 0.0, vmo2 = 0.0, vo = 0.0, sq = 0.0;
+                for (int j = 0; j < d; ++j) {
+                    const double diff = vp[j] - o[j];
+                    const double comb = (1.0 + z[p]) * vp[j] - z[p] * o[j];
+                    vv += vp[j] * vp[j];
+                    vmo2 += diff * diff;
+                    vo += vp[j] * o[j];
+                    sq += comb * comb;
                 }
-            }
-        }
-        for (int p = 0; p < N; ++p) {
-            const size_t idx = (size_t)bg * N + p;
-            const int live = p < len;
-            if (s_value) s_value[idx] = live ? acc_v[p] : 0.0;
-            if (s_key) s_key[idx] = live ? acc_k[p] : 0.0;
-            if (s_joint) {
-                double sj = joint_form ? acc_v[p] + acc_k[p] + acc_x[p] : acc_j[p];
-                s_joint[idx] = live ? sj : 0.0;
+                acc_v[p] += A2 * vv;                       /* Eq. 4 */
+                acc_k[p] += A2 * z[p] * z[p] * vmo2;       /* Eq. 5 */
+                acc_j[p] += A2 * sq;                       /* Eq. 6, completed square */
+                acc_x[p] += 2.0 * A2 * z[p] * (vv - vo);   /* Eq. 6, cross term */
             }
         }
         free(z); free(a); free(o);
-        free(acc_v); free(acc_k); free(acc_j); free(acc_x);
     }
+
+    /* Score of KV head g = sum over its query heads h in H(g) (Appendix A.5, second display). */
+    for (int bg = 0; bg < B * Hkv; ++bg) {
+        const int b = bg / Hkv, g = bg % Hkv;
+        const int len = seq_len_of(seq_lens, b, N);
+        for (int p = 0; p < N; ++p) {
+            double sv = 0.0, sk = 0.0, sj = 0.0, sx = 0.0;
+            for (int hh = 0; hh < G; ++hh) {
+                const size_t src = ((size_t)b * Hq + g * G + hh) * N + p;
+                sv += hv[src]; sk += hk[src]; sj += hj[src]; sx += hx[src];
+            }
+            const size_t idx = (size_t)bg * N + p;
+            const int live = p < len;
+            if (s_value) s_value[idx] = live ? sv : 0.0;
+            if (s_key) s_key[idx] = live ? sk : 0.0;
+            if (s_joint) s_joint[idx] = live ? (joint_form ? sv + sk + sx : sj) : 0.0;
+        }
+    }
+    free(hv); free(hk); free(hj); free(hx);
     return OBC_ORACLE_OK;
 }
 

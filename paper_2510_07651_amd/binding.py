@@ -1,0 +1,159 @@
+"""Thin ctypes binding of libobcache.so (C ABI in include/obcache.h).
+
+Argument marshalling only: tensors in, device pointers and sizes out.  Every step of
+the path runs in the HIP kernels; torch supplies device memory and the current
+stream.  There is no CPU fallback: a missing library is built once with hipcc, and a
+failure to build or load it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libobcache.so")
+
+OBC_VALUE, OBC_KEY, OBC_JOINT, OBC_ALL = 0, 1, 2, 3
+OBC_F32, OBC_BF16 = 0, 1
+OBC_OK, OBC_EINVAL, OBC_EUNSUPPORTED, OBC_EWORKSPACE, OBC_ELAUNCH = 0, -1, -2, -3, -4
+VARIANT_CODES = {"value": OBC_VALUE, "key": OBC_KEY, "joint": OBC_JOINT, "all": OBC_ALL}
+
+_lib = None
+
+
+class ObcError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s" % (where, obc_status_string(status)))
+
+
+def load_library():
+    """Loads (building first if absent) the HIP library and declares the ABI signatures."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        from . import build as _build
+        _build.build_library()
+    lib = ctypes.CDLL(LIB_PATH)
+    c_int, c_void_p, c_size_t = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    lib.obc_version.restype = c_int
+    lib.obc_status_string.restype = ctypes.c_char_p
+    lib.obc_status_string.argtypes = [c_int]
+    lib.obc_score_workspace_bytes.restype = c_int
+    lib.obc_score_workspace_bytes.argtypes = [c_int] * 8 + [ctypes.POINTER(c_size_t)]
+    lib.obc_score.restype = c_int
+    lib.obc_score.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p,
+                              c_int, c_int, i32p, c_void_p, c_size_t, c_void_p]
+    lib.obc_select.restype = c_int
+    lib.obc_select.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int, i32p, c_void_p]
+    lib.obc_compact.restype = c_int
+    lib.obc_compact.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int,
+                                c_int, c_void_p]
+    _lib = lib
+    return lib
+
+
+def obc_version() -> int:
+    return int(load_library().obc_version())
+
+
+def obc_status_string(status: int) -> str:
+    return load_library().obc_status_string(int(status)).decode()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return OBC_F32
+    if t.dtype == torch.bfloat16:
+        return OBC_BF16
+    raise TypeError("q, k, v must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _lens_arg(seq_lens: Optional[Sequence[int]], B: int):
+    if seq_lens is None:
+        return None
+    if len(seq_lens) != B:
+        raise ValueError("seq_lens needs one entry per sequence")
+    return (ctypes.c_int32 * B)(*[int(x) for x in seq_lens])
+
+
+def _stream_ptr(t: torch.Tensor) -> int:
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def _require_cuda(*tensors):
+    for t in tensors:
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous and on the GPU")
+
+
+def obc_score_workspace_bytes(B, N, W, Hq, Hkv, d, dtype, variant) -> int:
+    out = ctypes.c_size_t(0)
+    rc = load_library().obc_score_workspace_bytes(B, N, W, Hq, Hkv, d, dtype, variant, ctypes.byref(out))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_score_workspace_bytes")
+    return int(out.value)
+
+
+def obc_score(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, variant="joint", seq_lens=None,
+              scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """q [B,Hq,W,d], k,v [B,Hkv,N,d] -> scores [B,Hkv,N] fp32 ([3,B,Hkv,N] for variant "all")."""
+    _require_cuda(q, k, v)
+    B, Hq, W, d = q.shape
+    Bk, Hkv, N, dk = k.shape
+    if (Bk, dk) != (B, d) or v.shape != k.shape or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v shapes or dtypes disagree")
+    var = VARIANT_CODES[variant] if isinstance(variant, str) else int(variant)
+    dt = _dtype_code(q)
+    if workspace is None:
+        workspace = torch.empty(obc_score_workspace_bytes(B, N, W, Hq, Hkv, d, dt, var), dtype=torch.uint8,
+                                device=q.device)
+    if scores is None:
+        shape = (3, B, Hkv, N) if var == OBC_ALL else (B, Hkv, N)
+        scores = torch.empty(shape, dtype=torch.float32, device=q.device)
+    _require_cuda(scores, workspace)
+    rc = load_library().obc_score(q.data_ptr(), k.data_ptr(), v.data_ptr(), N, W, Hq, Hkv, d, var, scores.data_ptr(),
+                                  B, dt, _lens_arg(seq_lens, B), workspace.data_ptr(), workspace.numel(),
+                                  _stream_ptr(q))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_score")
+    return scores
+
+
+def obc_select(scores: torch.Tensor, budget: int, seq_lens=None,
+               keep_idx: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """scores [B,Hkv,N] fp32 -> keep_idx [B,Hkv,budget] int32 ascending."""
+    _require_cuda(scores)
+    if scores.dtype != torch.float32 or scores.dim() != 3:
+        raise ValueError("scores must be [B,Hkv,N] float32")
+    B, Hkv, N = scores.shape
+    if keep_idx is None:
+        keep_idx = torch.empty((B, Hkv, max(int(budget), 0)), dtype=torch.int32, device=scores.device)
+    rc = load_library().obc_select(scores.data_ptr(), int(budget), keep_idx.data_ptr(), B, Hkv, N,
+                                   _lens_arg(seq_lens, B), _stream_ptr(scores))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_select")
+    return keep_idx
+
+
+def obc_compact(k: torch.Tensor, v: torch.Tensor, keep_idx: torch.Tensor, k_out=None, v_out=None):
+    """k,v [B,Hkv,N,d], keep_idx [B,Hkv,budget] int32 -> (k_out, v_out) [B,Hkv,budget,d]."""
+    _require_cuda(k, v, keep_idx)
+    B, Hkv, N, d = k.shape
+    budget = keep_idx.shape[-1]
+    if keep_idx.dtype != torch.int32 or keep_idx.shape[:2] != (B, Hkv) or v.shape != k.shape:
+        raise ValueError("keep_idx must be [B,Hkv,budget] int32 matching k, v")
+    if k_out is None:
+        k_out = torch.empty((B, Hkv, budget, d), dtype=k.dtype, device=k.device)
+    if v_out is None:
+        v_out = torch.empty((B, Hkv, budget, d), dtype=v.dtype, device=v.device)
+    rc = load_library().obc_compact(k.data_ptr(), v.data_ptr(), keep_idx.data_ptr(), k_out.data_ptr(),
+                                    v_out.data_ptr(), B, Hkv, N, budget, d, _dtype_code(k), _stream_ptr(k))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_compact")
+    return k_out, v_out

@@ -1,0 +1,37 @@
+// K/V compaction (Appendix E, Algorithm 2: gather of the kept rows).  Pure byte moves:
+// each thread copies one 16-byte piece of one kept row with a 128-bit load and store.
+#include "internal.h"
+
+namespace obc {
+namespace {
+
+__global__ __launch_bounds__(256) void gather_rows(const uint4 *__restrict__ k, const uint4 *__restrict__ v,
+                                                   const int32_t *__restrict__ keep_idx, uint4 *__restrict__ k_out,
+                                                   uint4 *__restrict__ v_out, int N, int budget, int row_vec,
+                                                   size_t total_vec) {
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total_vec) return;
+    const size_t out_row = t / row_vec;             // (b*Hkv + g) * budget + j
+    const int c = (int)(t % row_vec);
+    const size_t bg = out_row / budget;
+    int p = keep_idx[out_row];
+    p = p < 0 ? 0 : (p >= N ? N - 1 : p);
+    const size_t src = (bg * N + p) * row_vec + c;
+    const uint4 *in = blockIdx.y == 0 ? k : v;
+    uint4 *out = blockIdx.y == 0 ? k_out : v_out;
+    out[t] = in[src];
+}
+
+}  // namespace
+
+hipError_t launch_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_out, void *v_out, int B,
+                          int Hkv, int N, int budget, int row_bytes, hipStream_t stream) {
+    const int row_vec = row_bytes / 16;
+    const size_t total = (size_t)B * Hkv * budget * row_vec;
+    const dim3 grid((unsigned)((total + 255) / 256), 2);
+    gather_rows<<<grid, dim3(256), 0, stream>>>((const uint4 *)k, (const uint4 *)v, keep_idx, (uint4 *)k_out,
+                                                (uint4 *)v_out, N, budget, row_vec, total);
+    return hipGetLastError();
+}
+
+}  // namespace obc

@@ -1,0 +1,65 @@
+// Internal declarations shared by the translation units of libobcache (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "obcache.h"
+
+namespace obc {
+
+// True lengths travel to the kernels by value (kernel-argument memory), so the
+// library needs no device allocation and no host-to-device copy of its own.
+struct SeqLens {
+    int32_t len[OBC_MAX_RAGGED_BATCH];
+};
+
+struct ScoreArgs {
+    const void *q, *k, *v;
+    float *scores;
+    int B, N, W, Hq, Hkv, d, G;
+    int variant;      // obc_variant_t
+    int dtype;        // obc_dtype_t
+    int ragged;       // 0: every sequence has length N
+    SeqLens lens;     // valid for b < B when ragged
+};
+
+// Workspace carve-up for obc_score; offsets in bytes from a 256-byte aligned base.
+struct ScoreWorkspace {
+    size_t row_max;    // float [B*Hq*W]      max over visible keys of the scaled logit (natural log units)
+    size_t row_sum;    // float [B*Hq*W]      sum over visible keys of exp(z - row_max)
+    size_t out_f32;    // float [B*Hq*W*d]    o_i = sum_p A_ip v_p
+    size_t out_rest_f32;  // float [B*Hq*W*d] attention output of the row over every key but its top-logit one
+    size_t rest_frac;  // float [B*Hq*W]      1 - A_{i,p*}: share of the row's attention not on its top-logit key
+    size_t top_token;  // int32 [B*Hq*W]      p*: lowest index among the keys attaining the row max
+    size_t out_bf16;   // bf16  [B*Hkv*Mpad*d] o_i rounded, rows padded per KV head to a multiple of 32 (matrix-core path)
+    size_t row_const;  // float [B*Hkv*Mpad*4] per padded row: log2-domain offset, ||o||^2, last visible key, spare
+    size_t partial;    // float [B*Hkv*splits*Mpad*(d+2)] split-sequence partial (max, sum, unnormalised O)
+    size_t total;
+    int m_pad;         // padded rows per KV head (multiple of 32)
+    int splits;        // sequence splits in the first sweep
+    int use_mfma;      // 1: matrix-core path, 0: plain path
+};
+
+int plan_score_workspace(int B, int N, int W, int Hq, int Hkv, int d, int dtype, int variant, ScoreWorkspace *ws);
+// Adds the matrix-core path's buffers to the plan, advancing *off (bytes).
+void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWorkspace *ws, size_t *off);
+
+// Launchers.  Each enqueues on `stream` and returns hipSuccess or the launch error.
+hipError_t launch_score_plain(const ScoreArgs &a, const ScoreWorkspace &ws, char *ws_base, hipStream_t stream);
+hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char *ws_base, hipStream_t stream);
+hipError_t launch_select(const float *scores, int budget, int32_t *keep_idx, int B, int Hkv, int N, int ragged,
+                         const SeqLens &lens, hipStream_t stream);
+hipError_t launch_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_out, void *v_out, int B,
+                          int Hkv, int N, int budget, int row_bytes, hipStream_t stream);
+
+__device__ __forceinline__ int seq_len_of(const SeqLens &lens, int ragged, int b, int N) {
+    return ragged ? lens.len[b] : N;
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t h) {
+    return __uint_as_float(((uint32_t)h) << 16);
+}
+
+}  // namespace obc

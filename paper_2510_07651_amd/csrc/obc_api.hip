@@ -1,0 +1,141 @@
+// Host side of the C ABI declared in include/obcache.h: argument validation, workspace
+// carve-up and kernel dispatch.  Nothing here allocates or synchronises.
+#include <cstdlib>
+#include <cstring>
+
+#include "internal.h"
+
+namespace obc {
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static int check_score_shape(int B, int N, int W, int Hq, int Hkv, int d, int dtype, int variant) {
+    if (B < 1 || N < 1 || W < 1 || Hq < 1 || Hkv < 1 || d < 1) return OBC_EINVAL;
+    if (Hq % Hkv != 0 || W > N) return OBC_EINVAL;
+    if (variant < OBC_VALUE || variant > OBC_ALL) return OBC_EINVAL;
+    if (dtype != OBC_F32 && dtype != OBC_BF16) return OBC_EUNSUPPORTED;
+    if (d != 64 && d != 128) return OBC_EUNSUPPORTED;
+    if (W > OBC_MAX_WINDOW || (Hq / Hkv) * W > OBC_MAX_GROUP_ROWS) return OBC_EUNSUPPORTED;
+    if ((long long)B * Hq > 65535 * 16LL || (long long)B * Hkv > 65535) return OBC_EUNSUPPORTED;
+    if ((long long)N > (1LL << 30)) return OBC_EUNSUPPORTED;
+    return OBC_OK;
+}
+
+static bool force_plain_path() {
+    const char *e = std::getenv("OBC_SCORE_PATH");   // "plain" routes bf16 d=128 through the vector-ALU kernels too
+    return e && std::strcmp(e, "plain") == 0;
+}
+
+int plan_score_workspace(int B, int N, int W, int Hq, int Hkv, int d, int dtype, int variant, ScoreWorkspace *ws) {
+    const int rc = check_score_shape(B, N, W, Hq, Hkv, d, dtype, variant);
+    if (rc != OBC_OK) return rc;
+    std::memset(ws, 0, sizeof(*ws));
+    const int G = Hq / Hkv;
+    const size_t rows = (size_t)B * Hq * W;
+    ws->use_mfma = (dtype == OBC_BF16 && d == 128 && !force_plain_path()) ? 1 : 0;
+    ws->m_pad = (G * W + 31) / 32 * 32;
+    size_t off = 0;
+    ws->row_max = off;  off = align_up(off + rows * sizeof(float), 256);
+    ws->row_sum = off;  off = align_up(off + rows * sizeof(float), 256);
+    ws->out_f32 = off;  off = align_up(off + rows * d * sizeof(float), 256);
+    ws->out_rest_f32 = off;  off = align_up(off + rows * d * sizeof(float), 256);
+    ws->rest_frac = off;  off = align_up(off + rows * sizeof(float), 256);
+    ws->top_token = off;  off = align_up(off + rows * sizeof(int32_t), 256);
+    if (ws->use_mfma) {
+        mfma_plan(B, N, W, Hq, Hkv, d, variant, ws, &off);
+    }
+    ws->total = align_up(off, 256);
+    return OBC_OK;
+}
+
+static int fill_lens(const int32_t *seq_lens_host, int B, int N, int min_len, int *ragged, SeqLens *lens) {
+    *ragged = 0;
+    if (!seq_lens_host) return N >= min_len ? OBC_OK : OBC_EINVAL;
+    if (B > OBC_MAX_RAGGED_BATCH) return OBC_EUNSUPPORTED;
+    for (int b = 0; b < B; ++b) {
+        const int L = seq_lens_host[b];
+        if (L > N || L < min_len) return OBC_EINVAL;
+        lens->len[b] = L;
+    }
+    *ragged = 1;
+    return OBC_OK;
+}
+
+}  // namespace obc
+
+using namespace obc;
+
+extern "C" {
+
+int obc_version(void) { return 100; }
+
+const char *obc_status_string(int status) {
+    switch (status) {
+        case OBC_OK: return "OBC_OK";
+        case OBC_EINVAL: return "OBC_EINVAL: invalid argument";
+        case OBC_EUNSUPPORTED: return "OBC_EUNSUPPORTED: shape or dtype not supported by the gfx950 kernels";
+        case OBC_EWORKSPACE: return "OBC_EWORKSPACE: workspace missing, misaligned or too small";
+        case OBC_ELAUNCH: return "OBC_ELAUNCH: HIP launch error";
+        default: return "unknown obcache status";
+    }
+}
+
+int obc_score_workspace_bytes(int B, int N, int W, int Hq, int Hkv, int d, int dtype, int variant,
+                              size_t *bytes_out) {
+    if (!bytes_out) return OBC_EINVAL;
+    ScoreWorkspace ws;
+    const int rc = plan_score_workspace(B, N, W, Hq, Hkv, d, dtype, variant, &ws);
+    if (rc != OBC_OK) return rc;
+    *bytes_out = ws.total;
+    return OBC_OK;
+}
+
+int obc_score(const void *q, const void *k, const void *v, int N, int W, int Hq, int Hkv, int d, int variant,
+              float *scores, int B, int dtype, const int32_t *seq_lens_host, void *workspace,
+              size_t workspace_bytes, void *hip_stream) {
+    if (!q || !k || !v || !scores) return OBC_EINVAL;
+    ScoreWorkspace ws;
+    int rc = plan_score_workspace(B, N, W, Hq, Hkv, d, dtype, variant, &ws);
+    if (rc != OBC_OK) return rc;
+    ScoreArgs a;
+    std::memset(&a, 0, sizeof(a));
+    rc = fill_lens(seq_lens_host, B, N, W, &a.ragged, &a.lens);
+    if (rc != OBC_OK) return rc;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < ws.total) return OBC_EWORKSPACE;
+    a.q = q; a.k = k; a.v = v; a.scores = scores;
+    a.B = B; a.N = N; a.W = W; a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.G = Hq / Hkv;
+    a.variant = variant; a.dtype = dtype;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const hipError_t e = ws.use_mfma ? launch_score_mfma(a, ws, (char *)workspace, stream)
+                                     : launch_score_plain(a, ws, (char *)workspace, stream);
+    return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
+}
+
+int obc_select(const float *scores, int budget, int32_t *keep_idx, int B, int Hkv, int N,
+               const int32_t *seq_lens_host, void *hip_stream) {
+    if (!scores || !keep_idx) return OBC_EINVAL;
+    if (B < 1 || Hkv < 1 || N < 1 || budget < 1 || budget > N) return OBC_EINVAL;
+    if ((long long)B * Hkv > 0x7fffffffLL / 2 || (long long)N > (1LL << 30)) return OBC_EUNSUPPORTED;
+    int ragged = 0;
+    SeqLens lens;
+    std::memset(&lens, 0, sizeof(lens));
+    const int rc = fill_lens(seq_lens_host, B, N, budget, &ragged, &lens);
+    if (rc != OBC_OK) return rc;
+    const hipError_t e = launch_select(scores, budget, keep_idx, B, Hkv, N, ragged, lens, (hipStream_t)hip_stream);
+    return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
+}
+
+int obc_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_out, void *v_out, int B, int Hkv,
+                int N, int budget, int d, int dtype, void *hip_stream) {
+    if (!k || !v || !keep_idx || !k_out || !v_out) return OBC_EINVAL;
+    if (B < 1 || Hkv < 1 || N < 1 || budget < 1 || d < 1) return OBC_EINVAL;
+    if (dtype != OBC_F32 && dtype != OBC_BF16) return OBC_EUNSUPPORTED;
+    const long long row_bytes = (long long)d * (dtype == OBC_F32 ? 4 : 2);
+    if (row_bytes % 16 != 0 || row_bytes > (1 << 20)) return OBC_EUNSUPPORTED;
+    if ((long long)B * Hkv * budget * (row_bytes / 16) > (1LL << 38)) return OBC_EUNSUPPORTED;
+    const hipError_t e = launch_compact(k, v, keep_idx, k_out, v_out, B, Hkv, N, budget, (int)row_bytes,
+                                        (hipStream_t)hip_stream);
+    return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
+}
+
+}  // extern "C"

@@ -141,7 +141,7 @@ def small_cases() -> List[Workload]:
                  sinks=4, outlier_channels=4, ragged=(700, 2100), pad_nan=True),
         Workload("s_bf16_qwen", B=1, Hq=14, Hkv=2, d=128, N=3000, W=64, dtype="bf16", budget=300, seed=15,
                  sinks=4, outlier_channels=4, needles=8),
-        Workload("s_bf16_w1", B=2, Hq=4, Hkv=4, d=128, N=1000, W=1, dtype="bf16", budget=100, seed=16, sinks=1),
+        Workload("s_bf16_w1", B=2, Hq=8, Hkv=4, d=128, N=1000, W=1, dtype="bf16", budget=100, seed=16, sinks=1),
         Workload("s_bf16_strong_sink", B=1, Hq=8, Hkv=2, d=128, N=1200, W=32, dtype="bf16", budget=150, seed=17,
                  sinks=4, shared_query=1.0),
         Workload("s_bf16_tiny", B=1, Hq=4, Hkv=1, d=128, N=40, W=32, dtype="bf16", budget=33, seed=18, sinks=1),

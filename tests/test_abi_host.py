@@ -1,0 +1,89 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, and
+rejects bad arguments on the host before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2510_07651_amd import binding as obc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return obc.load_library()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "obcache.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(obc_[a-z_]+)\s*\(", header))
+    assert {"obc_score", "obc_select", "obc_compact", "obc_score_workspace_bytes", "obc_status_string",
+            "obc_version"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert obc.obc_version() >= 100
+
+
+def test_status_strings(lib):
+    assert obc.obc_status_string(0) == "OBC_OK"
+    for code in (-1, -2, -3, -4):
+        assert obc.obc_status_string(code).startswith("OBC_E")
+    assert "unknown" in obc.obc_status_string(-99)
+
+
+def test_workspace_query_validation():
+    assert obc.obc_score_workspace_bytes(1, 512, 16, 1, 1, 64, obc.OBC_F32, obc.OBC_ALL) % 256 == 0
+    big = obc.obc_score_workspace_bytes(4, 32768, 32, 32, 8, 128, obc.OBC_BF16, obc.OBC_JOINT)
+    assert 0 < big < (1 << 30)
+    bad = [
+        (1, 512, 16, 3, 2, 64, obc.OBC_F32, obc.OBC_ALL, obc.OBC_EINVAL),        # Hq % Hkv != 0
+        (1, 8, 16, 1, 1, 64, obc.OBC_F32, obc.OBC_ALL, obc.OBC_EINVAL),          # W > N
+        (0, 512, 16, 1, 1, 64, obc.OBC_F32, obc.OBC_ALL, obc.OBC_EINVAL),        # B < 1
+        (1, 512, 16, 1, 1, 64, obc.OBC_F32, 7, obc.OBC_EINVAL),                  # variant
+        (1, 512, 16, 1, 1, 96, obc.OBC_F32, obc.OBC_ALL, obc.OBC_EUNSUPPORTED),  # head_dim
+        (1, 512, 16, 1, 1, 64, 5, obc.OBC_ALL, obc.OBC_EUNSUPPORTED),            # dtype
+        (1, 512, 65, 1, 1, 64, obc.OBC_F32, obc.OBC_ALL, obc.OBC_EUNSUPPORTED),  # window too long
+        (1, 512, 64, 16, 1, 64, obc.OBC_F32, obc.OBC_ALL, obc.OBC_EUNSUPPORTED), # G*W too large
+    ]
+    for *args, expect in bad:
+        with pytest.raises(obc.ObcError) as e:
+            obc.obc_score_workspace_bytes(*args)
+        assert e.value.status == expect, args
+
+
+def test_entry_points_reject_bad_arguments_before_launch(lib):
+    """Null pointers, bad lengths and missing workspace return error codes on a box with no GPU."""
+    fake = ctypes.c_void_p(4096)          # never dereferenced: validation fails first
+    lens = (ctypes.c_int32 * 2)(100, 5)
+    sc = lib.obc_score
+    assert sc(None, fake, fake, 512, 16, 1, 1, 64, 2, fake, 1, 0, None, fake, 1 << 30, None) == obc.OBC_EINVAL
+    assert sc(fake, fake, fake, 512, 16, 1, 1, 64, 2, None, 1, 0, None, fake, 1 << 30, None) == obc.OBC_EINVAL
+    # W > len_b for the second sequence
+    assert sc(fake, fake, fake, 512, 16, 1, 1, 64, 2, fake, 2, 0, lens, fake, 1 << 30, None) == obc.OBC_EINVAL
+    # len_b > N
+    lens2 = (ctypes.c_int32 * 1)(600)
+    assert sc(fake, fake, fake, 512, 16, 1, 1, 64, 2, fake, 1, 0, lens2, fake, 1 << 30, None) == obc.OBC_EINVAL
+    # workspace: null, misaligned, too small
+    assert sc(fake, fake, fake, 512, 16, 1, 1, 64, 2, fake, 1, 0, None, None, 1 << 30, None) == obc.OBC_EWORKSPACE
+    assert sc(fake, fake, fake, 512, 16, 1, 1, 64, 2, fake, 1, 0, None, ctypes.c_void_p(4100), 1 << 30,
+              None) == obc.OBC_EWORKSPACE
+    assert sc(fake, fake, fake, 512, 16, 1, 1, 64, 2, fake, 1, 0, None, fake, 16, None) == obc.OBC_EWORKSPACE
+    # ragged batch larger than the by-value table
+    many = (ctypes.c_int32 * 200)(*([512] * 200))
+    assert sc(fake, fake, fake, 512, 16, 1, 1, 64, 2, fake, 200, 0, many, fake, 1 << 40, None) == obc.OBC_EUNSUPPORTED
+
+    sel = lib.obc_select
+    assert sel(None, 4, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
+    assert sel(fake, 0, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
+    assert sel(fake, 17, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
+    short = (ctypes.c_int32 * 1)(3)
+    assert sel(fake, 4, fake, 1, 1, 16, short, None) == obc.OBC_EINVAL          # budget > len_b
+
+    cp = lib.obc_compact
+    assert cp(fake, fake, None, fake, fake, 1, 1, 16, 4, 64, 0, None) == obc.OBC_EINVAL
+    assert cp(fake, fake, fake, fake, fake, 1, 1, 16, 0, 64, 0, None) == obc.OBC_EINVAL
+    assert cp(fake, fake, fake, fake, fake, 1, 1, 16, 4, 6, 1, None) == obc.OBC_EUNSUPPORTED   # 12-byte rows
+    assert cp(fake, fake, fake, fake, fake, 1, 1, 16, 4, 64, 9, None) == obc.OBC_EUNSUPPORTED  # dtype

@@ -1,0 +1,121 @@
+"""GPU parity, element by element, against the fp64 CPU oracle on oracle-sized inputs.
+
+Every call goes through the C ABI (ctypes binding).  Tolerances: scores rel 1e-5 (fp32
+inputs) / 1e-3 (bf16 inputs, fp32 accumulation) measured as in parity_util.score_error;
+indices bit-exact given the same fp32 scores; byte-exact compaction.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_07651_amd import binding as obc
+from paper_2510_07651_amd import synth
+
+from parity_util import (TOL, check_keep_idx_valid, check_selection_against_oracle_scores, oracle_scores,
+                         score_error, to_device)
+
+pytestmark = pytest.mark.gpu
+
+CASES = {w.name: w for w in synth.small_cases() + synth.paper_configs()[:2]}
+
+
+def _run_case(wl):
+    x = synth.make_inputs(wl)
+    dev = to_device(x)
+    lens = x["seq_lens"]
+    tol = TOL[wl.dtype]
+    ref = oracle_scores(x)
+    all3 = obc.obc_score(dev["q"], dev["k"], dev["v"], "all", seq_lens=lens)
+    torch.cuda.synchronize()
+    assert all3.shape == (3, wl.B, wl.Hkv, wl.N)
+    worst = {}
+    for vi, name in enumerate(synth.VARIANTS):
+        gpu = all3[vi].cpu().numpy()
+        assert np.isfinite(gpu).all() and (gpu >= 0).all(), name
+        worst[name], where = score_error(gpu, ref[vi], wl.budget, lens, tol)
+        assert worst[name] <= tol, "%s %s: err %.3g at %s" % (wl.name, name, worst[name], where)
+        # single-variant calls give the same bits as the all-variant call
+        one = obc.obc_score(dev["q"], dev["k"], dev["v"], name, seq_lens=lens)
+        assert torch.equal(one, all3[vi]), name
+        # selection: bit-exact vs the oracle's select on the very same fp32 scores
+        keep = obc.obc_select(all3[vi].contiguous(), wl.budget, seq_lens=lens)
+        keep_np = keep.cpu().numpy()
+        check_keep_idx_valid(keep_np, wl.budget, lens, wl.N)
+        np.testing.assert_array_equal(keep_np, oracle.select(gpu, wl.budget, lens))
+        # and consistent with the oracle's own scores outside the tolerance band
+        check_selection_against_oracle_scores(keep_np, ref[vi], wl.budget, lens, tol)
+    # compaction: byte-exact gather
+    k_out, v_out = obc.obc_compact(dev["k"], dev["v"], keep)
+    as_bits = (lambda t: t.view(torch.int16)) if wl.dtype == "bf16" else (lambda t: t.view(torch.int32))
+    kref, vref = oracle.compact(as_bits(x["k"]).numpy(), as_bits(x["v"]).numpy(), keep_np)
+    np.testing.assert_array_equal(as_bits(k_out).cpu().numpy(), kref)
+    np.testing.assert_array_equal(as_bits(v_out).cpu().numpy(), vref)
+    return worst
+
+
+@pytest.mark.parametrize("name", list(CASES))
+def test_score_select_compact_match_oracle(name):
+    worst = _run_case(CASES[name])
+    print(name, {k: "%.2e" % v for k, v in worst.items()})
+
+
+def test_deterministic_bits():
+    wl = CASES["s_bf16_llama"]
+    dev = to_device(synth.make_inputs(wl))
+    a = obc.obc_score(dev["q"], dev["k"], dev["v"], "all")
+    b = obc.obc_score(dev["q"], dev["k"], dev["v"], "all")
+    assert torch.equal(a, b)
+
+
+def test_plain_path_env_switch(monkeypatch):
+    """The vector-ALU path serves bf16 head_dim-128 inputs too when asked to; it must agree with the oracle."""
+    monkeypatch.setenv("OBC_SCORE_PATH", "plain")
+    _run_case(CASES["s_bf16_ragged"])
+
+
+def test_select_crafted_ties_and_specials():
+    dev = torch.device("cuda")
+    rng = np.random.default_rng(5)
+    cases = []
+    s = np.floor(rng.random((2, 3, 5000)) * 7).astype(np.float32)            # heavy ties across the cut
+    cases.append((s, 777, [5000, 4100]))
+    cases.append((np.full((1, 2, 4097), 3.25, np.float32), 1000, None))       # all equal
+    z = np.zeros((1, 1, 9000), np.float32); z[0, 0, ::7] = -0.0; z[0, 0, [11, 4999, 8999]] = 1.0
+    cases.append((z, 10, None))                                               # zeros of both signs
+    n = rng.standard_normal((1, 2, 3000)).astype(np.float32); n[0, :, ::5] = np.nan; n[0, 0, 7] = -np.inf
+    cases.append((n, 2500, None))                                             # NaN below -inf, negatives
+    e = rng.random((2, 2, 64)).astype(np.float32)
+    cases.append((e, 64, None))                                               # budget == N
+    cases.append((e, 1, [64, 1]))                                             # budget 1, len 1
+    big = rng.random((1, 1, 200000)).astype(np.float32) ** 8                  # long head, tiny values
+    cases.append((big, 4096, None))
+    d = rng.random((1, 1, 70000)).astype(np.float32); d[0, 0, 1000:60000] = d[0, 0, 1000]
+    cases.append((d, 30000, None))                                            # 59000 duplicates straddling the cut
+    for s, budget, lens in cases:
+        keep = obc.obc_select(torch.from_numpy(s).to(dev), budget, seq_lens=lens).cpu().numpy()
+        np.testing.assert_array_equal(keep, oracle.select(s, budget, lens))
+
+
+def test_compact_fp32_and_edge_rows():
+    dev = torch.device("cuda")
+    g = torch.Generator().manual_seed(3)
+    k = torch.randn(2, 3, 100, 64, generator=g); v = torch.randn(2, 3, 100, 64, generator=g)
+    idx = torch.stack([torch.stack([torch.randperm(100, generator=g)[:17].sort().values for _ in range(3)])
+                       for _ in range(2)]).to(torch.int32)
+    idx[0, 0, 0] = 0; idx[0, 0, -1] = 99
+    ko, vo = obc.obc_compact(k.to(dev), v.to(dev), idx.to(dev))
+    kref, vref = oracle.compact(k.numpy(), v.numpy(), idx.numpy())
+    np.testing.assert_array_equal(ko.cpu().numpy(), kref)
+    np.testing.assert_array_equal(vo.cpu().numpy(), vref)
+
+
+def test_runtime_errors_surface():
+    dev = torch.device("cuda")
+    q = torch.zeros(1, 2, 4, 128, device=dev, dtype=torch.bfloat16)
+    k = torch.zeros(1, 1, 64, 128, device=dev, dtype=torch.bfloat16)
+    with pytest.raises(obc.ObcError) as e:
+        obc.obc_score(q, k, k.clone(), "joint", seq_lens=[3])        # W > len
+    assert e.value.status == obc.OBC_EINVAL
+    with pytest.raises(obc.ObcError):
+        obc.obc_select(torch.zeros(1, 1, 8, device=dev), 9)
