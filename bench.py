@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the OBCache hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic batch already resident in HBM:
+obc_score (joint variant) -> obc_select -> obc_compact, through the C ABI.  The default
+workload is the one the headline metric is quoted on: c3, one LLaMA-3.1-8B-shaped layer
+(32 query / 8 KV heads, d=128, W=32, bf16), batch 4, N=32768, budget 2048.
+
+Prints ONE JSON line: whole-path throughput in scored KV tokens/s, the HBM roofline of the
+scoring call (algorithmic bytes: K and V once, Q, scores) from durations measured here with
+events on the launch stream, per-kernel durations, and the fp64 CPU oracle timed on a
+bounded sample of the same workload (a reported baseline, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c3")
+    ap.add_argument("--variant", default="joint")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=8, help="KV heads of sequence 0 the oracle is timed on")
+    return ap.parse_args()
+
+
+def timed(fn, iters, torch):
+    """Average milliseconds per call of fn(i), events on the current (launch) stream."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(iters):
+        fn(i)
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2510_07651_amd import binding as obc
+    from paper_2510_07651_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(3)
+    obc.load_library()
+    dev = torch.device("cuda:0")
+    wl = synth.config(args.workload)
+    B, Hq, Hkv, d, N, W = wl.B, wl.Hq, wl.Hkv, wl.d, wl.N, wl.W
+    lens = synth.seq_lens_of(wl)
+    tokens = sum(lens) if lens else B * N
+
+    # Two independent input sets, alternated, so that no cache can hold a step's K/V from the step before.
+    sets = []
+    for layer in range(2):
+        x = synth.make_inputs(wl, layer=layer)
+        sets.append({k: (v.to(dev) if torch.is_tensor(v) else v) for k, v in x.items()})
+    var = obc.VARIANT_CODES[args.variant]
+    dt = obc.OBC_BF16 if wl.dtype == "bf16" else obc.OBC_F32
+    ws = torch.empty(obc.obc_score_workspace_bytes(B, N, W, Hq, Hkv, d, dt, var), dtype=torch.uint8, device=dev)
+    nvar = 3 if var == obc.OBC_ALL else 1
+    scores = torch.empty((nvar, B, Hkv, N) if nvar == 3 else (B, Hkv, N), dtype=torch.float32, device=dev)
+    sel_scores = scores[2] if nvar == 3 else scores
+    keep = torch.empty((B, Hkv, wl.budget), dtype=torch.int32, device=dev)
+    k_out = torch.empty((B, Hkv, wl.budget, d), dtype=sets[0]["k"].dtype, device=dev)
+    v_out = torch.empty_like(k_out)
+
+    def score(i, mask=None):
+        s = sets[i & 1]
+        obc.obc_score(s["q"], s["k"], s["v"], var, seq_lens=lens, scores=scores, workspace=ws, stage_mask=mask)
+
+    def select(i):
+        obc.obc_select(sel_scores, wl.budget, seq_lens=lens, keep_idx=keep)
+
+    def compact(i):
+        s = sets[i & 1]
+        obc.obc_compact(s["k"], s["v"], keep, k_out=k_out, v_out=v_out)
+
+    def step(i):
+        score(i)
+        select(i)
+        compact(i)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = tokens / (ms_per_step * 1e-3)
+
+    # Per-stage device durations (events on the launch stream), same alternating inputs.
+    it = max(args.steps, 10)
+    ms = {
+        "obc_score": timed(score, it, torch),
+        "sweep1": timed(lambda i: score(i, obc.OBC_STAGE_SWEEP1), it, torch),
+        "combine": timed(lambda i: score(i, obc.OBC_STAGE_COMBINE), it, torch),
+        "sweep2": timed(lambda i: score(i, obc.OBC_STAGE_SWEEP2), it, torch),
+        "obc_select": timed(select, it, torch),
+        "obc_compact": timed(compact, it, torch),
+    }
+    esize = 2 if wl.dtype == "bf16" else 4
+    head_tokens = tokens * Hkv
+    algo_bytes = head_tokens * 2 * d * esize + B * Hq * W * d * esize + nvar * B * Hkv * N * 4
+    achieved = algo_bytes / (ms["obc_score"] * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % wl.name)
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("obc_score_bytes_per_call")
+    roofline = {
+        "bound": "hbm", "kernel": "obc_score = mfma_sweep1 + mfma_combine + mfma_sweep2",
+        "achieved": round(achieved, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+        "frac": round(achieved / PEAK_HBM_GBPS, 4), "traffic": traffic,
+        "algorithmic_bytes": algo_bytes,
+        "kernel_ms": {k: round(v, 4) for k, v in ms.items()},
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        x = synth.make_inputs(wl, layer=0)
+        G = Hq // Hkv
+        nh = min(args.cpu_heads, Hkv)
+        L0 = lens[0] if lens else N
+        qs, ks, vs = x["q"][0:1, : nh * G], x["k"][0:1, :nh], x["v"][0:1, :nh]
+        c0 = time.perf_counter()
+        s = oracle.score(qs, ks, vs, seq_lens=[L0] if lens else None)
+        keep_ref = oracle.select(s[2].astype("float32"), wl.budget, [L0] if lens else None)
+        c1 = time.perf_counter()
+        frac_heads = nh / Hkv
+        cpu = {
+            "value": round(L0 * frac_heads / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "sequence 0, %d of %d KV heads (%d head-tokens), fp64 score (3 variants) + select; %.1f s"
+                      % (nh, Hkv, L0 * nh, c1 - c0),
+        }
+        del keep_ref
+
+    out = {
+        "metric": "scored KV tokens/sec (all heads) at N=32K; achieved HBM GB/s vs peak",
+        "value": round(value, 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "B": B, "Hq": Hq, "Hkv": Hkv, "d": d, "N": N, "W": W, "budget": wl.budget,
+                   "variant": args.variant, "path": "score+select+compact"},
+        "head_tokens_per_s": round(head_tokens / (ms_per_step * 1e-3), 1),
+        "score_only_tokens_per_s": round(tokens / (ms["obc_score"] * 1e-3), 1),
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

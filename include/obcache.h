@@ -94,6 +94,25 @@ int obc_score(const void *q, const void *k, const void *v,
               void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Measurement hook: obc_score restricted to some of its stages, so that each kernel
+ * of the two-sweep scoring path can be timed on its own with events around the call.
+ * Same arguments and checks as obc_score; `stage_mask` is a bit set of
+ *   OBC_STAGE_SWEEP1   window attention statistics and outputs (Section 3), per sequence split
+ *   OBC_STAGE_COMBINE  merge of the splits into per-row constants
+ *   OBC_STAGE_SWEEP2   the scores of Eq. 4-6 from those constants
+ * A later stage reads what the earlier ones left in `workspace`, so the first call on a
+ * workspace must include all earlier stages.  obc_score == all three.
+ */
+#define OBC_STAGE_SWEEP1 1
+#define OBC_STAGE_COMBINE 2
+#define OBC_STAGE_SWEEP2 4
+#define OBC_STAGE_ALL 7
+int obc_score_stages(const void *q, const void *k, const void *v,
+                     int N, int W, int Hq, int Hkv, int d, int variant, float *scores,
+                     int B, int dtype, const int32_t *seq_lens_host,
+                     void *workspace, size_t workspace_bytes, void *hip_stream, int stage_mask);
+
+/*
  * Top-`budget` selection per (b, KV head) (Section 3 "Cache Eviction";
  * Algorithm 2).
  *   scores    [B, Hkv, N] fp32

@@ -49,6 +49,8 @@ def load_library():
     lib.obc_score.restype = c_int
     lib.obc_score.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p,
                               c_int, c_int, i32p, c_void_p, c_size_t, c_void_p]
+    lib.obc_score_stages.restype = c_int
+    lib.obc_score_stages.argtypes = lib.obc_score.argtypes + [c_int]
     lib.obc_select.restype = c_int
     lib.obc_select.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int, i32p, c_void_p]
     lib.obc_compact.restype = c_int
@@ -100,9 +102,15 @@ def obc_score_workspace_bytes(B, N, W, Hq, Hkv, d, dtype, variant) -> int:
     return int(out.value)
 
 
+OBC_STAGE_SWEEP1, OBC_STAGE_COMBINE, OBC_STAGE_SWEEP2, OBC_STAGE_ALL = 1, 2, 4, 7
+
+
 def obc_score(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, variant="joint", seq_lens=None,
-              scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """q [B,Hq,W,d], k,v [B,Hkv,N,d] -> scores [B,Hkv,N] fp32 ([3,B,Hkv,N] for variant "all")."""
+              scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+              stage_mask: Optional[int] = None) -> torch.Tensor:
+    """q [B,Hq,W,d], k,v [B,Hkv,N,d] -> scores [B,Hkv,N] fp32 ([3,B,Hkv,N] for variant "all").
+
+    stage_mask (measurement hook) routes the call through obc_score_stages."""
     _require_cuda(q, k, v)
     B, Hq, W, d = q.shape
     Bk, Hkv, N, dk = k.shape
@@ -117,9 +125,12 @@ def obc_score(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, variant="joint"
         shape = (3, B, Hkv, N) if var == OBC_ALL else (B, Hkv, N)
         scores = torch.empty(shape, dtype=torch.float32, device=q.device)
     _require_cuda(scores, workspace)
-    rc = load_library().obc_score(q.data_ptr(), k.data_ptr(), v.data_ptr(), N, W, Hq, Hkv, d, var, scores.data_ptr(),
-                                  B, dt, _lens_arg(seq_lens, B), workspace.data_ptr(), workspace.numel(),
-                                  _stream_ptr(q))
+    args = (q.data_ptr(), k.data_ptr(), v.data_ptr(), N, W, Hq, Hkv, d, var, scores.data_ptr(), B, dt,
+            _lens_arg(seq_lens, B), workspace.data_ptr(), workspace.numel(), _stream_ptr(q))
+    if stage_mask is None:
+        rc = load_library().obc_score(*args)
+    else:
+        rc = load_library().obc_score_stages(*args, int(stage_mask))
     if rc != OBC_OK:
         raise ObcError(rc, "obc_score")
     return scores

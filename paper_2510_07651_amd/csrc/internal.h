@@ -22,6 +22,7 @@ struct ScoreArgs {
     int variant;      // obc_variant_t
     int dtype;        // obc_dtype_t
     int ragged;       // 0: every sequence has length N
+    int stage_mask;   // OBC_STAGE_* bits to run
     SeqLens lens;     // valid for b < B when ragged
 };
 
@@ -33,12 +34,17 @@ struct ScoreWorkspace {
     size_t out_rest_f32;  // float [B*Hq*W*d] attention output of the row over every key but its top-logit one
     size_t rest_frac;  // float [B*Hq*W]      1 - A_{i,p*}: share of the row's attention not on its top-logit key
     size_t top_token;  // int32 [B*Hq*W]      p*: lowest index among the keys attaining the row max
-    size_t out_bf16;   // bf16  [B*Hkv*Mpad*d] o_i rounded, rows padded per KV head to a multiple of 32 (matrix-core path)
-    size_t row_const;  // float [B*Hkv*Mpad*4] per padded row: log2-domain offset, ||o||^2, last visible key, spare
-    size_t partial;    // float [B*Hkv*splits*Mpad*(d+2)] split-sequence partial (max, sum, unnormalised O)
+    size_t out_bf16;   // bf16  [2][B*Hkv*m_pad*d]  o_i as two bf16 pieces (high, residual); rows of a KV head padded to a multiple of 32
+    size_t row_const;  // float [B*Hkv*m_pad*4]  per padded row: 2*(max + log2 sum) in log2 units, ||o||^2, last visible key, spare
+    size_t part_ml;    // float [B*Hkv*splits*m_pad*2]  per sequence split: row max (log2 units), row sum
+    size_t part_o;     // float [B*Hkv*splits*m_pad*d]  per sequence split: unnormalised output
+    size_t planes;     // float [n_chunks*nv*B*Hkv*N]   per row-chunk partial scores (only when n_chunks > 1)
     size_t total;
     int m_pad;         // padded rows per KV head (multiple of 32)
+    int n_chunks;      // row chunks of 128 rows per KV head
     int splits;        // sequence splits in the first sweep
+    int split_len;     // tokens per split (multiple of 64)
+    int range_len;     // tokens per workgroup in the second sweep (multiple of 64)
     int use_mfma;      // 1: matrix-core path, 0: plain path
 };
 

@@ -93,7 +93,15 @@ int obc_score_workspace_bytes(int B, int N, int W, int Hq, int Hkv, int d, int d
 int obc_score(const void *q, const void *k, const void *v, int N, int W, int Hq, int Hkv, int d, int variant,
               float *scores, int B, int dtype, const int32_t *seq_lens_host, void *workspace,
               size_t workspace_bytes, void *hip_stream) {
+    return obc_score_stages(q, k, v, N, W, Hq, Hkv, d, variant, scores, B, dtype, seq_lens_host, workspace,
+                            workspace_bytes, hip_stream, OBC_STAGE_ALL);
+}
+
+int obc_score_stages(const void *q, const void *k, const void *v, int N, int W, int Hq, int Hkv, int d, int variant,
+                     float *scores, int B, int dtype, const int32_t *seq_lens_host, void *workspace,
+                     size_t workspace_bytes, void *hip_stream, int stage_mask) {
     if (!q || !k || !v || !scores) return OBC_EINVAL;
+    if (stage_mask < 1 || stage_mask > OBC_STAGE_ALL) return OBC_EINVAL;
     ScoreWorkspace ws;
     int rc = plan_score_workspace(B, N, W, Hq, Hkv, d, dtype, variant, &ws);
     if (rc != OBC_OK) return rc;
@@ -106,6 +114,7 @@ int obc_score(const void *q, const void *k, const void *v, int N, int W, int Hq,
     a.B = B; a.N = N; a.W = W; a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.G = Hq / Hkv;
     a.variant = variant; a.dtype = dtype;
     hipStream_t stream = (hipStream_t)hip_stream;
+    a.stage_mask = stage_mask;
     const hipError_t e = ws.use_mfma ? launch_score_mfma(a, ws, (char *)workspace, stream)
                                      : launch_score_plain(a, ws, (char *)workspace, stream);
     return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;

@@ -1,6 +1,840 @@
-// Matrix-core scoring path (bf16 inputs, head_dim 128) -- placeholder until the kernels land.
+// Matrix-core scoring path for bf16 caches with head_dim 128 (gfx950, wave64).
+//
+// The scores of Eq. 4-6 need, for every (window row i, token p) pair, the softmax weight
+// A_ip, the logit Z_ip and the cross term v_p . o_i, where A and o_i depend on sums over
+// ALL tokens of the row (Section 3).  So the cache is swept twice:
+//
+//   sweep 1  (mfma_sweep1)   per (KV head, 128-row chunk, sequence split): S^T = K Q^T on
+//            the matrix cores, online softmax per row, O^T += V^T P^T on the matrix cores;
+//            emits a partial (row max, row sum, unnormalised O) per split.
+//   combine  (mfma_combine)  merges the splits: final max, sum, o_i (fp32 and bf16),
+//            ||o_i||^2, and the constants the second sweep needs per row.
+//   sweep 2  (mfma_sweep2)   per (KV head, chunk, token range): Z = Q K^T and the cross
+//            terms O V^T on the matrix cores, with tokens on the lane axis of the
+//            accumulators so that the sum over window rows and query heads (Eq. 9,
+//            Appendix A.5) runs down registers; A^2 = exp2(2 log2e Z - 2 log2(max-shifted
+//            sum)) and the three scores are formed in fp32.
+//
+// Both sweeps walk their tokens in blocks of 32 with a software pipeline: while the vector
+// ALUs turn block n's accumulators into softmax weights (sweep 1) or scores (sweep 2), the
+// matrix cores already work on block n+1's contractions (and, in sweep 1, on block n-1's
+// P V product).  The streams of one step are independent, so they sit in one basic block
+// and the instruction scheduler interleaves them.  K/V tiles of 64 tokens travel
+// HBM -> LDS with direct-to-LDS loads, two steps ahead of their use.
+//
+// Precision.  The matrix cores take bf16 operands, and rows whose attention is
+// concentrated on a few keys are sensitive to that rounding (the scores of those keys
+// depend on v_p - o_i, a difference of nearly equal vectors).  Two operands are therefore
+// fed as an exact-enough pair of bf16 pieces (high part + residual, 16 significant bits):
+// the softmax weights P in O^T += V^T P^T, and o_i in the cross term O V^T.  Both pieces
+// reuse the same LDS operand, so the cost is matrix-core issue slots only.
+// ||v_p - o_i||^2 is evaluated as ||v_p||^2 - 2 v_p.o^_i + ||o^_i||^2 with o^_i the
+// two-piece value used by the matrix cores in BOTH the cross term and the norm, so the
+// expression is the exact squared distance to o^_i.
+//
+// A and Z never touch HBM.  All sums have a fixed order: results are bit-reproducible.
 #include "internal.h"
+
 namespace obc {
-void mfma_plan(int, int, int, int, int, int, int, ScoreWorkspace *ws, size_t *) { ws->use_mfma = 0; }
-hipError_t launch_score_mfma(const ScoreArgs &, const ScoreWorkspace &, char *, hipStream_t) { return hipErrorNotSupported; }
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short i16x4;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __bf16 bf16_2 __attribute__((ext_vector_type(2)));
+typedef float f32_2 __attribute__((ext_vector_type(2)));
+
+constexpr int kD = 128;                 // head_dim
+constexpr int kRowBytes = kD * 2;       // one bf16 K or V row
+constexpr int kTileTok = 64;            // tokens per LDS tile (two blocks of 32)
+constexpr int kTileBytes = kTileTok * kRowBytes;   // 16 KB
+constexpr int kThreads = 256;           // 4 waves; wave w owns row block 4*chunk + w (32 window rows)
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kInvSqrtD = 0.08838834764831845f;   // 1/sqrt(128)
+
+// LDS map (bytes): two K tiles, then two V tiles.
+constexpr int kLdsK0 = 0, kLdsK1 = kTileBytes, kLdsV0 = 2 * kTileBytes, kLdsV1 = 3 * kTileBytes;
+constexpr int kLdsTiles = 4 * kTileBytes;           // 64 KB
+
+enum Swizzle { kXor16 = 0, kRot4 = 1 };
+
+// LDS tiles hold 64 rows of 256 B.  Row R keeps its 16-byte piece c at slot
+//   kXor16: c ^ (R & 15)         -- conflict-free when 16 lanes read the same piece of 16 consecutive rows
+//   kRot4 : (c + 4 (R & 3)) & 15 -- conflict-free when 32 lanes read 64 contiguous bytes of 4 consecutive rows
+__device__ __forceinline__ int piece_of(int swz, int R, int slot) {
+    return swz == kXor16 ? (slot ^ (R & 15)) : ((slot - 4 * (R & 3)) & 15);
+}
+
+__device__ __forceinline__ uint32_t lds_offset_of(const void *p) {
+    return (uint32_t)(size_t)(const __attribute__((address_space(3))) char *)p;
+}
+
+// One direct-to-LDS transfer: every lane supplies the address of 16 bytes in global
+// memory; the wave's 1 KB lands contiguously at LDS byte `lds_off` (lane l at +16 l).
+// Issued from inline assembly so that the compiler's wait-count bookkeeping does not tie
+// later LDS reads of OTHER tiles to these transfers; the kernels wait for them
+// explicitly (wait_async_loads + barrier) before the tile is read.
+__device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_off), "v"(gptr) : "memory");
+}
+__device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Asynchronous copy of one 64-row tile.  Each wave issues four transfers; lane l of
+// transfer n lands at row 4 (4 wave + n) + l / 16, slot l % 16, and picks the global piece
+// that belongs in that slot.  Rows past `last_row` re-read `last_row` (memory beyond the
+// true length is never touched).
+template <int SWZ>
+__device__ __forceinline__ void tile_load_async(const char *__restrict__ head_base, int t0, int last_row,
+                                                uint32_t lds_tile, int wave, int lane) {
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        const int R = (wave * 4 + n) * 4 + (lane >> 4);
+        const int c = piece_of(SWZ, R, lane & 15);
+        int row = t0 + R;
+        row = row > last_row ? last_row : row;
+        dma16(head_base + (size_t)row * kRowBytes + c * 16, lds_tile + (wave * 4 + n) * 1024);
+    }
+}
+
+// Per-lane byte offset, inside a kXor16 tile, of piece 2 kk + half of row (lane % 32) of a
+// 32-row block; add 32 * 256 for the tile's second block.  16-byte matrix-core operand:
+// K as the A operand of K Q^T, K and V as B operands of Q K^T and O V^T.
+__device__ __forceinline__ int row_piece_offset(int lane, int kk) {
+    const int R = lane & 31, c = 2 * kk + (lane >> 5);
+    return R * kRowBytes + ((c ^ (R & 15)) << 4);
+}
+
+// Per-lane byte offset, inside a kRot4 tile, of the transposing read that serves the A
+// operand of O^T += V^T P^T for head_dim block ddb: 16 lanes fetch a 4-token x 16-element
+// block and each lane gets one column of it (4 tokens of one head_dim index).  Add
+// (first token of the 4-token group) * 256.
+__device__ __forceinline__ int vt_piece_offset(int lane, int ddb) {
+    const int i = lane & 15, sub = (lane >> 4) & 1, half = lane >> 5;
+    const int rq = i >> 2;                              // token inside the group == (row & 3)
+    const int c = ddb * 4 + sub * 2 + ((i & 3) >> 1);
+    const int slot = (c + 4 * rq) & 15;
+    return (4 * half + rq) * kRowBytes + (slot << 4) + ((i & 1) << 3);
+}
+
+__device__ __forceinline__ bf16x8 lds_read16(const char *p) { return *(const bf16x8 *)p; }
+
+// The 8 tokens of a k-step in the order in which the accumulator of K Q^T holds them:
+// rows r0 + 4 half + {0..3} and r0 + 8 + 4 half + {0..3}.
+__device__ __forceinline__ bf16x8 lds_read_vt(const char *p) {
+    union { bf16x8 v; i16x4 h[2]; } u;
+    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(p));
+    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(p + 8 * kRowBytes));
+    return u.v;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    const f32_2 f = {lo, hi};
+    const bf16_2 r = __builtin_convertvector(f, bf16_2);   // v_cvt_pk_bf16_f32, round to nearest even
+    return *(const uint32_t *)&r;
+}
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32); }
+__device__ __forceinline__ f32x16 zero16() {
+    f32x16 z;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+    return z;
+}
+
+union PiecePair { bf16x8 v; uint32_t u[4]; };
+
+// Pins a value loaded from global memory as "consumed here", so that the wait for its load
+// is placed here (before the pipelined loops) and not inside them, where it would also
+// wait for the direct-to-LDS tile loads in flight.
+__device__ __forceinline__ void settle(const bf16x8 &x) { asm volatile("" ::"v"(x)); }
+__device__ __forceinline__ void settle(const float &x) { asm volatile("" ::"v"(x)); }
+
+// Interleaving recipe for one pipeline step, applied to the step's basic block: after two
+// LDS reads, repeat {1 matrix-core op, `valu` vector-ALU ops, `ds` LDS reads}.
+template <int kSlots, int kValu, int kDs>
+__device__ __forceinline__ void interleave_hint() {
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+    for (int i = 0; i < kSlots; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, kValu, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, kDs, 0);
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Sweep 1
+// ------------------------------------------------------------------------------------
+struct Sweep1Regs {
+    bf16x8 q[8];          // stationary B operand: this lane's query row, pieces 2 kk + half
+    f32x16 oacc[4];       // O^T accumulators: head_dim block x 16 registers
+    f32x16 s_cur;         // raw q.k of the block whose softmax is due
+    PiecePair phi[2], plo[2];   // two-piece softmax weights of the previous block, per k-step
+    float m_raw, lsum;    // running max of raw q.k; this lane's share of the running sum
+    float alpha;          // rescale of oacc still owed from the previous step (1 = none)
+    bool rescale;         // uniform: some row of the wave owes a rescale
+};
+
+// One pipeline step n of sweep 1 (PH = n mod 4 fixes every LDS slot at compile time):
+//   matrix cores: O^T += V^T P^T of block n-1, S^T = K Q^T of block n+1
+//   vector ALUs : online softmax of block n
+// Odd steps first wait for the tiles issued two steps earlier and start the next two.
+template <int PH, bool kMasked, bool kNeedO>
+__device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uint32_t lds0, int n, int t_begin,
+                                            int t_end, int last_row, int vis, const char *kh, const char *vh,
+                                            const int (&koff)[8], const int (&voff)[4], int wave, int lane,
+                                            bool wave_active) {
+    constexpr int kKSlot = (PH == 0 || PH == 3) ? kLdsK0 : kLdsK1;      // tile of block n+1
+    constexpr int kKBlk = (PH == 0 || PH == 2) ? 1 : 0;
+    constexpr int kVSlot = (PH == 1 || PH == 2) ? kLdsV0 : kLdsV1;      // tile of block n-1
+    constexpr int kVBlk = (PH == 0 || PH == 2) ? 1 : 0;
+    const float c2 = kLog2e * kInvSqrtD;
+    const int half = lane >> 5;
+
+    if (PH & 1) {
+        wait_async_loads();
+        __syncthreads();
+        const int t = (n + 1) >> 1;                     // this step starts K tile t+1 and V tile t
+        const int tk = t_begin + (t + 1) * kTileTok, tv = t_begin + t * kTileTok;
+        if (tk < t_end) tile_load_async<kXor16>(kh, tk, last_row, lds0 + (PH == 1 ? kLdsK0 : kLdsK1), wave, lane);
+        if (kNeedO && tv < t_end) tile_load_async<kRot4>(vh, tv, last_row, lds0 + (PH == 1 ? kLdsV1 : kLdsV0), wave, lane);
+    }
+    if (!wave_active) return;
+    // The running max moved in the previous step: bring the accumulated O^T (blocks <= n-2)
+    // to the new reference before block n-1, whose weights already use it, is added.
+    // Kept as the only branch of the step so that everything below is one basic block.
+    if (kNeedO && R.rescale) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) R.oacc[i][r] *= R.alpha;
+    }
+
+    // ---- matrix cores: block n-1 ----
+    if (kNeedO) {
+#pragma unroll
+        for (int ddb = 0; ddb < 4; ++ddb)
+#pragma unroll
+            for (int sx = 0; sx < 2; ++sx) {
+                const bf16x8 a = lds_read_vt(smem + kVSlot + (kVBlk * 32 + 16 * sx) * kRowBytes + voff[ddb]);
+                R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.phi[sx].v, R.oacc[ddb], 0, 0, 0);
+                R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.plo[sx].v, R.oacc[ddb], 0, 0, 0);
+            }
+    }
+    // ---- matrix cores: block n+1 ----
+    f32x16 s_next = zero16();
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        const bf16x8 a = lds_read16(smem + kKSlot + kKBlk * 32 * kRowBytes + koff[kk]);
+        s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.q[kk], s_next, 0, 0, 0);
+    }
+    // ---- vector ALUs: block n ----
+    f32x16 s = R.s_cur;
+    if (kMasked) {
+        const int tok0 = t_begin + n * 32;      // register r holds token tok0 + 8 (r / 4) + 4 half + r % 4
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int tok = tok0 + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (tok > vis || tok >= t_end) s[r] = -INFINITY;
+        }
+    }
+    float mx = max3(s[0], s[1], s[2]);
+#pragma unroll
+    for (int r = 3; r < 15; r += 2) mx = max3(mx, s[r], s[r + 1]);
+    mx = fmaxf(mx, s[15]);
+    mx = fmaxf(mx, other_half(mx));
+    const float m_new = fmaxf(R.m_raw, mx);
+    const bool moved = m_new > R.m_raw;
+    float alpha = __builtin_amdgcn_exp2f((R.m_raw - m_new) * c2);     // exp2(-inf) = 0
+    float mref = m_new * c2;
+    if (kMasked) {                                                     // rows with nothing visible yet
+        alpha = moved ? alpha : 1.0f;
+        mref = m_new == -INFINITY ? 0.f : mref;
+    }
+    R.m_raw = m_new;
+    float p[16], psum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -mref));
+        psum += p[r];
+    }
+    R.lsum = fmaf(R.lsum, alpha, psum);
+    if (kNeedO) {
+        // P = hi + lo: hi keeps the top 16 bits of the fp32 weight (a bf16 by truncation),
+        // lo is the exact remainder rounded to bf16.
+#pragma unroll
+        for (int sx = 0; sx < 2; ++sx)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float p0 = p[8 * sx + 2 * e], p1 = p[8 * sx + 2 * e + 1];
+                const uint32_t h0 = __float_as_uint(p0) & 0xffff0000u, h1 = __float_as_uint(p1) & 0xffff0000u;
+                R.phi[sx].u[e] = __builtin_amdgcn_perm(h1, h0, 0x07060302u);     // {h0 >> 16, h1 >> 16}
+                R.plo[sx].u[e] = pack_bf16(p0 - __uint_as_float(h0), p1 - __uint_as_float(h1));
+            }
+        R.alpha = alpha;
+        R.rescale = __any(moved);      // uniform and rare once the running max has settled
+    }
+    R.s_cur = s_next;
+    interleave_hint<kNeedO ? 24 : 8, kNeedO ? 6 : 12, kNeedO ? 2 : 1>();
+}
+
+// Grid: x = sequence split, y = 128-row chunk, z = (b, KV head).
+template <bool kNeedO>
+__global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__restrict__ q,
+                                                           const uint16_t *__restrict__ k,
+                                                           const uint16_t *__restrict__ v, int N, int W, int Hq,
+                                                           int Hkv, int ragged, SeqLens lens, int split_len,
+                                                           int n_splits, int m_pad, float *__restrict__ part_ml,
+                                                           float *__restrict__ part_o) {
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+    const int split = blockIdx.x, chunk = blockIdx.y, bg = blockIdx.z;
+    const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv, M = G * W;
+    const int len = seq_len_of(lens, ragged, b, N);
+    const int t_begin = split * split_len;
+    if (t_begin >= len) return;                                  // uniform: nothing of this split is live
+    const int t_end = min(t_begin + split_len, len);
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, half = lane >> 5;
+    const int rb = chunk * 4 + wave;                             // row block of this wave
+    const int row = rb * 32 + (lane & 31);                       // window row (i) owned by this lane
+    const bool wave_active = rb * 32 < M;                        // uniform
+    const bool row_valid = row < M;
+    // Last key the row may see (Eq. 9 window rows are causal).  Padded rows carry a zero
+    // query and see everything: they stay finite and are discarded later.
+    const int vis = row_valid ? len - W + (row % W) : len - 1;
+    int vis_min = vis;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) vis_min = min(vis_min, __shfl_xor(vis_min, off));
+    vis_min = __builtin_amdgcn_readfirstlane(min(vis_min, t_end - 1));
+
+    const char *kh = (const char *)k + (size_t)bg * N * kRowBytes;
+    const char *vh = (const char *)v + (size_t)bg * N * kRowBytes;
+    const uint32_t lds0 = lds_offset_of(smem);
+
+    int koff[8], voff[4];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) koff[kk] = row_piece_offset(lane, kk);
+#pragma unroll
+    for (int ddb = 0; ddb < 4; ++ddb) voff[ddb] = vt_piece_offset(lane, ddb);
+
+    Sweep1Regs R;
+    {
+        const char *qrow = (const char *)q + (((size_t)b * Hq + (size_t)g * G) * W + row) * kRowBytes;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            if (row_valid) R.q[kk] = *(const bf16x8 *)(qrow + (2 * kk + half) * 16);
+            else R.q[kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) R.oacc[i] = zero16();
+#pragma unroll
+    for (int sx = 0; sx < 2; ++sx)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { R.phi[sx].u[e] = 0; R.plo[sx].u[e] = 0; }
+    R.m_raw = -INFINITY;
+    R.lsum = 0.f;
+    R.alpha = 1.0f;
+    R.rescale = false;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) settle(R.q[kk]);
+
+    // Prologue: the step before block 0 multiplies zero weights with whatever the second V
+    // tile holds, so that tile is cleared; K tile 0 is fetched and block 0's S^T formed.
+    for (int e = threadIdx.x; e < kTileBytes / 16; e += kThreads) ((uint4 *)(smem + kLdsV1))[e] = make_uint4(0, 0, 0, 0);
+    tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane);
+    wait_async_loads();
+    __syncthreads();
+    if (t_begin + kTileTok < t_end) tile_load_async<kXor16>(kh, t_begin + kTileTok, len - 1, lds0 + kLdsK1, wave, lane);
+    if (kNeedO) tile_load_async<kRot4>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane);
+    R.s_cur = zero16();
+    if (wave_active) {
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            const bf16x8 a = lds_read16(smem + kLdsK0 + koff[kk]);
+            R.s_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.q[kk], R.s_cur, 0, 0, 0);
+        }
+    }
+
+    const int n_blk = (t_end - t_begin + 31) / 32;
+    const int n_total = (n_blk + 3) & ~3;
+    int n_plain = (vis_min + 1 - t_begin) / 32;       // leading blocks every row of this wave sees in full
+    n_plain = max(0, min(n_plain, n_blk)) & ~3;
+#define OBC_S1_ARGS smem, lds0, n, t_begin, t_end, len - 1, vis, kh, vh, koff, voff, wave, lane, wave_active
+    int n = 0;
+    for (; n < n_plain; n += 4) {
+        sweep1_step<0, false, kNeedO>(R, OBC_S1_ARGS); ++n;
+        sweep1_step<1, false, kNeedO>(R, OBC_S1_ARGS); ++n;
+        sweep1_step<2, false, kNeedO>(R, OBC_S1_ARGS); ++n;
+        sweep1_step<3, false, kNeedO>(R, OBC_S1_ARGS); n -= 3;
+    }
+    for (; n < n_total; n += 4) {
+        sweep1_step<0, true, kNeedO>(R, OBC_S1_ARGS); ++n;
+        sweep1_step<1, true, kNeedO>(R, OBC_S1_ARGS); ++n;
+        sweep1_step<2, true, kNeedO>(R, OBC_S1_ARGS); ++n;
+        sweep1_step<3, true, kNeedO>(R, OBC_S1_ARGS); n -= 3;
+    }
+#undef OBC_S1_ARGS
+    if (!wave_active) return;
+    if (kNeedO) {      // drain: P V of the last block (phase 3: second block of the tile in V slot 1)
+        if (R.rescale) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) R.oacc[i][r] *= R.alpha;
+        }
+#pragma unroll
+        for (int ddb = 0; ddb < 4; ++ddb)
+#pragma unroll
+            for (int sx = 0; sx < 2; ++sx) {
+                const bf16x8 a = lds_read_vt(smem + kLdsV1 + (32 + 16 * sx) * kRowBytes + voff[ddb]);
+                R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.phi[sx].v, R.oacc[ddb], 0, 0, 0);
+                R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.plo[sx].v, R.oacc[ddb], 0, 0, 0);
+            }
+    }
+
+    const float c2 = kLog2e * kInvSqrtD;
+    const float lrow = R.lsum + other_half(R.lsum);
+    const size_t prow = ((size_t)bg * n_splits + split) * m_pad + row;
+    if (half == 0) {
+        part_ml[prow * 2 + 0] = R.m_raw * c2;    // log2 units; -inf when the split holds no visible key
+        part_ml[prow * 2 + 1] = lrow;
+    }
+    if (kNeedO) {
+        float *dst = part_o + prow * kD;
+#pragma unroll
+        for (int ddb = 0; ddb < 4; ++ddb)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int dd = ddb * 32 + 8 * r4 + 4 * half;
+                *(float4 *)(dst + dd) = make_float4(R.oacc[ddb][4 * r4], R.oacc[ddb][4 * r4 + 1],
+                                                    R.oacc[ddb][4 * r4 + 2], R.oacc[ddb][4 * r4 + 3]);
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Combine: one 128-thread block per (KV head, padded row); thread = head_dim element.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ part_ml,
+                                                    const float *__restrict__ part_o, int N, int W, int Hq, int Hkv,
+                                                    int ragged, SeqLens lens, int split_len, int n_splits,
+                                                    int m_pad, int need_o, float *__restrict__ row_max,
+                                                    float *__restrict__ row_sum, float *__restrict__ out_f32,
+                                                    uint16_t *__restrict__ out_bf16, float *__restrict__ row_const) {
+    __shared__ float red[2];
+    const int row = blockIdx.x, bg = blockIdx.y;
+    const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv, M = G * W;
+    const int len = seq_len_of(lens, ragged, b, N);
+    const int dd = threadIdx.x;
+    const size_t crow = (size_t)bg * m_pad + row;
+    const size_t lo_plane = (size_t)gridDim.y * m_pad * kD;   // residual pieces follow the high pieces
+    if (row >= M) {                                   // padded row: weightless in the second sweep
+        out_bf16[crow * kD + dd] = 0;
+        out_bf16[lo_plane + crow * kD + dd] = 0;
+        if (dd == 0) {
+            row_const[crow * 4 + 0] = 1e30f;
+            row_const[crow * 4 + 1] = 0.f;
+            row_const[crow * 4 + 2] = __int_as_float(-1);
+            row_const[crow * 4 + 3] = 0.f;
+        }
+        return;
+    }
+    const int live_splits = (len + split_len - 1) / split_len;
+    float m = -INFINITY;
+    for (int s = 0; s < live_splits; ++s) m = fmaxf(m, part_ml[(((size_t)bg * n_splits + s) * m_pad + row) * 2]);
+    float l = 0.f, o = 0.f;
+    for (int s = 0; s < live_splits; ++s) {
+        const size_t prow = ((size_t)bg * n_splits + s) * m_pad + row;
+        const float w = exp2f(part_ml[prow * 2] - m);             // 0 for splits hidden from this row
+        l = fmaf(w, part_ml[prow * 2 + 1], l);
+        if (need_o) o = fmaf(w, part_o[prow * kD + dd], o);
+    }
+    o = o / l;
+    // o^ = hi + lo, the pair of bf16 pieces the second sweep feeds to the matrix cores.
+    const uint16_t ob = (uint16_t)(__float_as_uint(o) >> 16);
+    const float ohi = bf16_bits_to_float(ob);
+    const uint16_t olo = (uint16_t)(pack_bf16(o - ohi, 0.f) & 0xffffu);
+    const float of = ohi + bf16_bits_to_float(olo);
+    float sq = of * of;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off);
+    if ((dd & 63) == 0) red[dd >> 6] = sq;
+    __syncthreads();
+    const size_t grow = ((size_t)b * Hq + (size_t)g * G) * W + row;
+    out_f32[grow * kD + dd] = o;
+    out_bf16[crow * kD + dd] = ob;
+    out_bf16[lo_plane + crow * kD + dd] = olo;
+    if (dd == 0) {
+        row_max[grow] = m * 0.6931471805599453f;      // natural-log units
+        row_sum[grow] = l;
+        row_const[crow * 4 + 0] = 2.0f * (m + log2f(l));   // A_ip^2 = exp2(2 log2e Z_ip - this)
+        row_const[crow * 4 + 1] = red[0] + red[1];         // ||o^_i||^2
+        row_const[crow * 4 + 2] = __int_as_float(len - W + (row % W));
+        row_const[crow * 4 + 3] = 0.f;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Sweep 2
+// ------------------------------------------------------------------------------------
+// Sum of squares of the 8 bf16 values in a 16-byte operand piece.
+__device__ __forceinline__ float sumsq8(const bf16x8 x, float acc) {
+    union { bf16x8 v; bf16x2 h[4]; } u;
+    u.v = x;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_fdot2_f32_bf16(u.h[e], u.h[e], acc, false);
+    return acc;
+}
+
+struct Sweep2Regs {
+    bf16x8 q[8], ohi[8], olo[8];   // stationary A operands of this wave's row block
+    float c_m2[16], c_oo[16];      // per accumulator register: 2 (max + log2 sum), ||o^||^2 of its row
+    f32x16 z_cur, vo_cur;          // raw q.k and o^.v of the block whose scores are due
+    float vv_cur;                  // this lane's half of ||v||^2 of its token in that block
+};
+
+// One pipeline step n of sweep 2 (PH = n mod 4 fixes the LDS slots):
+//   matrix cores: Z = Q K^T and O V^T of block n+1 (+ ||v||^2 on the dot-product unit)
+//   vector ALUs : scores of block n, summed over this wave's 32 rows, parked in LDS
+template <int PH, bool kMasked, int kVariant>
+__device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uint32_t lds0, int n, int n_blk,
+                                            int t_begin, int t_end, int last_row, const int *vis_i, const char *kh,
+                                            const char *vh, const int (&koff)[8], int wave, int lane,
+                                            bool wave_active, float *plane_w) {
+    constexpr int kNv = kVariant == OBC_ALL ? 3 : 1;
+    constexpr bool kDoV = kVariant == OBC_VALUE || kVariant == OBC_ALL;
+    constexpr bool kDoK = kVariant == OBC_KEY || kVariant == OBC_ALL;
+    constexpr bool kDoJ = kVariant == OBC_JOINT || kVariant == OBC_ALL;
+    constexpr bool kNeedVO = kDoK || kDoJ;
+    constexpr int kSlot = (PH == 0 || PH == 3) ? 0 : 1;               // tile of block n+1
+    constexpr int kBlk = (PH == 0 || PH == 2) ? 1 : 0;
+    constexpr int kKBase = (kSlot ? kLdsK1 : kLdsK0) + kBlk * 32 * kRowBytes;
+    constexpr int kVBase = (kSlot ? kLdsV1 : kLdsV0) + kBlk * 32 * kRowBytes;
+    const int half = lane >> 5;
+    const float c2x2 = 2.0f * kLog2e * kInvSqrtD;
+
+    if (PH & 1) {
+        wait_async_loads();
+        __syncthreads();
+        const int tn = t_begin + (((n + 1) >> 1) + 1) * kTileTok;     // first token of the tile to start now
+        if (tn < t_end) {
+            tile_load_async<kXor16>(kh, tn, last_row, lds0 + (PH == 1 ? kLdsK0 : kLdsK1), wave, lane);
+            tile_load_async<kXor16>(vh, tn, last_row, lds0 + (PH == 1 ? kLdsV0 : kLdsV1), wave, lane);
+        }
+    }
+    if (!wave_active) {
+        if (half == 0 && n < n_blk) {
+#pragma unroll
+            for (int c = 0; c < kNv; ++c) plane_w[(n * 32 + lane) * kNv + c] = 0.f;
+        }
+        return;
+    }
+
+    // ---- matrix cores: block n+1 ----
+    f32x16 z_next = zero16(), vo_next = zero16();
+    float vv_next = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        const bf16x8 kb = lds_read16(smem + kKBase + koff[kk]);
+        z_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.q[kk], kb, z_next, 0, 0, 0);
+    }
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        const bf16x8 vb = lds_read16(smem + kVBase + koff[kk]);
+        vv_next = sumsq8(vb, vv_next);
+        if (kNeedVO) {
+            vo_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.ohi[kk], vb, vo_next, 0, 0, 0);
+            vo_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.olo[kk], vb, vo_next, 0, 0, 0);
+        }
+    }
+
+    // ---- vector ALUs: block n ----
+    const float vv = R.vv_cur + other_half(R.vv_cur);          // ||v_p||^2 of this lane's token
+    const int tok = t_begin + n * 32 + (lane & 31);
+    float acc_v = 0.f, acc_k = 0.f, acc_j = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        float a2 = __builtin_amdgcn_exp2f(fmaf(R.z_cur[r], c2x2, -R.c_m2[r]));   // A_ip^2
+        if (kMasked) {
+            const int i = wave * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+            if (tok > vis_i[i] || tok >= t_end) a2 = 0.f;
+        }
+        const float zz = R.z_cur[r] * kInvSqrtD;                                  // Z_ip
+        if (kDoV) acc_v += a2;
+        if (kDoK) {
+            const float nrm = fmaf(R.vo_cur[r], -2.0f, vv + R.c_oo[r]);           // ||v_p - o^_i||^2
+            acc_k = fmaf(a2 * zz * zz, fmaxf(nrm, 0.f), acc_k);
+        }
+        if (kDoJ) {
+            // ||(1+Z) v - Z o^||^2 = (1+Z)^2 ||v||^2 - 2 Z (1+Z) v.o^ + Z^2 ||o^||^2
+            const float y = zz + 1.0f;
+            const float t1 = zz * R.vo_cur[r];
+            const float t2 = fmaf(t1, -2.0f, y * vv);
+            const float t3 = fmaf(zz * R.c_oo[r], zz, y * t2);
+            acc_j = fmaf(a2, fmaxf(t3, 0.f), acc_j);
+        }
+    }
+    if (kDoV) { acc_v *= vv; acc_v += other_half(acc_v); }
+    if (kDoK) acc_k += other_half(acc_k);
+    if (kDoJ) acc_j += other_half(acc_j);
+    if (half == 0 && n < n_blk) {
+        float *pw = plane_w + (n * 32 + lane) * kNv;
+        int c = 0;
+        if (kDoV) pw[c++] = acc_v;
+        if (kDoK) pw[c++] = acc_k;
+        if (kDoJ) pw[c++] = acc_j;
+    }
+    R.z_cur = z_next;
+    R.vo_cur = vo_next;
+    R.vv_cur = vv_next;
+    interleave_hint<kNeedVO ? 24 : 8, kNeedVO ? 10 : 12, 1>();
+}
+
+// kVariant: OBC_VALUE / OBC_KEY / OBC_JOINT / OBC_ALL.  Grid: x = token range, y = chunk, z = (b, KV head).
+// With one chunk the scores go straight to `scores`; with several, each chunk writes its
+// own plane and mfma_sum_planes adds them in chunk order.
+template <int kVariant>
+__global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__restrict__ q,
+                                                           const uint16_t *__restrict__ k,
+                                                           const uint16_t *__restrict__ v, int N, int W, int Hq,
+                                                           int Hkv, int ragged, SeqLens lens, int range_len, int m_pad,
+                                                           const uint16_t *__restrict__ out_bf16,
+                                                           const float *__restrict__ row_const,
+                                                           float *__restrict__ dst, size_t variant_stride,
+                                                           size_t chunk_stride) {
+    constexpr int kNv = kVariant == OBC_ALL ? 3 : 1;
+    constexpr bool kNeedVO = kVariant != OBC_VALUE;
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    float *vis_s = (float *)(smem + kLdsTiles);                // [128] last visible key of each row of the chunk
+    float *plane = vis_s + 128;                                // [4 waves][range_len][kNv]
+
+    const int range = blockIdx.x, chunk = blockIdx.y, bg = blockIdx.z;
+    const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv, M = G * W;
+    const int len = seq_len_of(lens, ragged, b, N);
+    const int t_begin = range * range_len;
+    const int t_stop = min(t_begin + range_len, N);            // scores are written for [t_begin, t_stop)
+    float *out = dst + (size_t)chunk * chunk_stride + (size_t)bg * N;
+
+    if (t_begin >= len) {                                      // uniform: only padded positions here
+        for (int t = t_begin + threadIdx.x; t < t_stop; t += kThreads)
+#pragma unroll
+            for (int c = 0; c < kNv; ++c) out[c * variant_stride + t] = 0.f;
+        return;
+    }
+    const int t_end = min(t_begin + range_len, len);
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, half = lane >> 5;
+    const int rb = chunk * 4 + wave;
+    const bool wave_active = rb * 32 < M;                      // uniform
+    const int arow = rb * 32 + (lane & 31);                    // row whose A-operand pieces this lane holds
+    const size_t cbase = (size_t)bg * m_pad;
+
+    const char *kh = (const char *)k + (size_t)bg * N * kRowBytes;
+    const char *vh = (const char *)v + (size_t)bg * N * kRowBytes;
+    const uint32_t lds0 = lds_offset_of(smem);
+
+    int koff[8];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) koff[kk] = row_piece_offset(lane, kk);
+
+    Sweep2Regs R;
+    {
+        const bool ok = arow < M;
+        const char *qrow = (const char *)q + (((size_t)b * Hq + (size_t)g * G) * W + arow) * kRowBytes;
+        const char *orow = (const char *)out_bf16 + (cbase + arow) * kRowBytes;
+        const size_t lo_plane = (size_t)gridDim.z * m_pad * kRowBytes;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            R.q[kk] = ok ? *(const bf16x8 *)(qrow + (2 * kk + half) * 16) : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            if (kNeedVO) {
+                R.ohi[kk] = ok ? *(const bf16x8 *)(orow + (2 * kk + half) * 16) : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+                R.olo[kk] = ok ? *(const bf16x8 *)(orow + lo_plane + (2 * kk + half) * 16) : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            }
+        }
+    }
+    // Constants of the 16 rows this lane meets in the accumulators: row rb*32 + 8 (r/4) + 4 half + r%4.
+    int vis_min = 0x7fffffff;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int i = rb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const bool ok = wave_active && i < m_pad;
+        R.c_m2[r] = ok ? row_const[(cbase + i) * 4 + 0] : 1e30f;
+        R.c_oo[r] = ok ? row_const[(cbase + i) * 4 + 1] : 0.f;
+        const int vi = ok ? __float_as_int(row_const[(cbase + i) * 4 + 2]) : -1;
+        if (vi >= 0) vis_min = min(vis_min, vi);
+    }
+    vis_min = min(vis_min, __shfl_xor(vis_min, 32));
+    vis_min = __builtin_amdgcn_readfirstlane(min(vis_min, t_end - 1));
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+        settle(R.q[kk]);
+        if (kNeedVO) { settle(R.ohi[kk]); settle(R.olo[kk]); }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { settle(R.c_m2[r]); settle(R.c_oo[r]); }
+    if (threadIdx.x < 128) {
+        const int i = chunk * 128 + threadIdx.x;
+        vis_s[threadIdx.x] = i < m_pad ? row_const[(cbase + i) * 4 + 2] : __int_as_float(-1);
+    }
+    const int *vis_i = (const int *)vis_s;
+    float *plane_w = plane + (size_t)wave * range_len * kNv;
+
+    // Prologue: tile 0, then block 0's contractions.
+    tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane);
+    tile_load_async<kXor16>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane);
+    wait_async_loads();
+    __syncthreads();
+    if (t_begin + kTileTok < t_end) {
+        tile_load_async<kXor16>(kh, t_begin + kTileTok, len - 1, lds0 + kLdsK1, wave, lane);
+        tile_load_async<kXor16>(vh, t_begin + kTileTok, len - 1, lds0 + kLdsV1, wave, lane);
+    }
+    R.z_cur = zero16();
+    R.vo_cur = zero16();
+    R.vv_cur = 0.f;
+    if (wave_active) {
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            const bf16x8 kb = lds_read16(smem + kLdsK0 + koff[kk]);
+            R.z_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.q[kk], kb, R.z_cur, 0, 0, 0);
+        }
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            const bf16x8 vb = lds_read16(smem + kLdsV0 + koff[kk]);
+            R.vv_cur = sumsq8(vb, R.vv_cur);
+            if (kNeedVO) {
+                R.vo_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.ohi[kk], vb, R.vo_cur, 0, 0, 0);
+                R.vo_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.olo[kk], vb, R.vo_cur, 0, 0, 0);
+            }
+        }
+    }
+
+    const int n_blk = (t_end - t_begin + 31) / 32;
+    const int n_total = (n_blk + 3) & ~3;
+    int n_plain = (vis_min + 1 - t_begin) / 32;
+    n_plain = max(0, min(n_plain, n_blk)) & ~3;
+#define OBC_S2_ARGS smem, lds0, n, n_blk, t_begin, t_end, len - 1, vis_i, kh, vh, koff, wave, lane, wave_active, plane_w
+    int n = 0;
+    for (; n < n_plain; n += 4) {
+        sweep2_step<0, false, kVariant>(R, OBC_S2_ARGS); ++n;
+        sweep2_step<1, false, kVariant>(R, OBC_S2_ARGS); ++n;
+        sweep2_step<2, false, kVariant>(R, OBC_S2_ARGS); ++n;
+        sweep2_step<3, false, kVariant>(R, OBC_S2_ARGS); n -= 3;
+    }
+    for (; n < n_total; n += 4) {
+        sweep2_step<0, true, kVariant>(R, OBC_S2_ARGS); ++n;
+        sweep2_step<1, true, kVariant>(R, OBC_S2_ARGS); ++n;
+        sweep2_step<2, true, kVariant>(R, OBC_S2_ARGS); ++n;
+        sweep2_step<3, true, kVariant>(R, OBC_S2_ARGS); n -= 3;
+    }
+#undef OBC_S2_ARGS
+    __syncthreads();
+    for (int t = threadIdx.x; t < t_stop - t_begin; t += kThreads) {
+        const bool live = t_begin + t < t_end;
+#pragma unroll
+        for (int c = 0; c < kNv; ++c) {
+            float s = 0.f;
+            if (live)
+                s = (plane[((size_t)0 * range_len + t) * kNv + c] + plane[((size_t)1 * range_len + t) * kNv + c]) +
+                    (plane[((size_t)2 * range_len + t) * kNv + c] + plane[((size_t)3 * range_len + t) * kNv + c]);
+            out[c * variant_stride + t_begin + t] = s;
+        }
+    }
+}
+
+// scores[c][idx] = sum over chunks of planes[chunk][c][idx], in chunk order.
+__global__ __launch_bounds__(256) void mfma_sum_planes(const float *__restrict__ planes, int n_chunks,
+                                                       size_t chunk_stride, size_t total, float *__restrict__ scores) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    float s = 0.f;
+    for (int c = 0; c < n_chunks; ++c) s += planes[(size_t)c * chunk_stride + i];
+    scores[i] = s;
+}
+
+template <int kVariant>
+hipError_t launch_sweep2(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStream_t stream) {
+    constexpr int nv = kVariant == OBC_ALL ? 3 : 1;
+    const size_t lds = kLdsTiles + 128 * sizeof(float) + (size_t)4 * ws.range_len * nv * sizeof(float);
+    hipError_t e = hipFuncSetAttribute((const void *)mfma_sweep2<kVariant>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    const size_t plane_elems = (size_t)a.B * a.Hkv * a.N;
+    float *dst = ws.n_chunks > 1 ? (float *)(base + ws.planes) : a.scores;
+    const size_t chunk_stride = ws.n_chunks > 1 ? plane_elems * nv : 0;
+    const dim3 grid((a.N + ws.range_len - 1) / ws.range_len, ws.n_chunks, a.B * a.Hkv);
+    mfma_sweep2<kVariant><<<grid, dim3(kThreads), lds, stream>>>(
+        (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens,
+        ws.range_len, ws.m_pad, (const uint16_t *)(base + ws.out_bf16), (const float *)(base + ws.row_const), dst,
+        plane_elems, chunk_stride);
+    e = hipGetLastError();
+    if (e != hipSuccess || ws.n_chunks == 1) return e;
+    const size_t total = plane_elems * nv;
+    mfma_sum_planes<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(dst, ws.n_chunks, chunk_stride, total, a.scores);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWorkspace *ws, size_t *off) {
+    auto align_up = [](size_t x, size_t a) { return (x + a - 1) / a * a; };
+    const int BH = B * Hkv;
+    const int nv = variant == OBC_ALL ? 3 : 1;
+    ws->n_chunks = (ws->m_pad + 127) / 128;
+    int splits = (512 + BH * ws->n_chunks - 1) / (BH * ws->n_chunks);
+    const int max_splits = (N + 511) / 512;
+    splits = splits < 1 ? 1 : (splits > max_splits ? max_splits : splits);
+    ws->split_len = ((N + splits - 1) / splits + kTileTok - 1) / kTileTok * kTileTok;
+    ws->splits = (N + ws->split_len - 1) / ws->split_len;
+    ws->range_len = 512;
+    const size_t rows = (size_t)BH * ws->m_pad;
+    ws->out_bf16 = *off;  *off = align_up(*off + 2 * rows * d * 2, 256);   // high pieces, then residual pieces
+    ws->row_const = *off; *off = align_up(*off + rows * 4 * sizeof(float), 256);
+    ws->part_ml = *off;   *off = align_up(*off + rows * ws->splits * 2 * sizeof(float), 256);
+    ws->part_o = *off;    *off = align_up(*off + rows * ws->splits * d * sizeof(float), 256);
+    ws->planes = *off;
+    if (ws->n_chunks > 1) *off = align_up(*off + (size_t)ws->n_chunks * nv * BH * N * sizeof(float), 256);
+}
+
+hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStream_t stream) {
+    const bool need_o = a.variant != OBC_VALUE;
+    float *part_ml = (float *)(base + ws.part_ml), *part_o = (float *)(base + ws.part_o);
+    hipError_t e = hipSuccess;
+    if (a.stage_mask & OBC_STAGE_SWEEP1) {
+        const size_t lds = kLdsTiles;
+        const dim3 grid(ws.splits, ws.n_chunks, a.B * a.Hkv);
+        const void *fn = need_o ? (const void *)mfma_sweep1<true> : (const void *)mfma_sweep1<false>;
+        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        if (need_o)
+            mfma_sweep1<true><<<grid, dim3(kThreads), lds, stream>>>(
+                (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged,
+                a.lens, ws.split_len, ws.splits, ws.m_pad, part_ml, part_o);
+        else
+            mfma_sweep1<false><<<grid, dim3(kThreads), lds, stream>>>(
+                (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged,
+                a.lens, ws.split_len, ws.splits, ws.m_pad, part_ml, part_o);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (a.stage_mask & OBC_STAGE_COMBINE) {
+        mfma_combine<<<dim3(ws.m_pad, a.B * a.Hkv), dim3(128), 0, stream>>>(
+            part_ml, part_o, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, ws.split_len, ws.splits, ws.m_pad,
+            need_o ? 1 : 0, (float *)(base + ws.row_max), (float *)(base + ws.row_sum),
+            (float *)(base + ws.out_f32), (uint16_t *)(base + ws.out_bf16), (float *)(base + ws.row_const));
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (!(a.stage_mask & OBC_STAGE_SWEEP2)) return hipSuccess;
+    switch (a.variant) {
+        case OBC_VALUE: return launch_sweep2<OBC_VALUE>(a, ws, base, stream);
+        case OBC_KEY: return launch_sweep2<OBC_KEY>(a, ws, base, stream);
+        case OBC_JOINT: return launch_sweep2<OBC_JOINT>(a, ws, base, stream);
+        default: return launch_sweep2<OBC_ALL>(a, ws, base, stream);
+    }
+}
+
 }  // namespace obc

@@ -283,11 +283,14 @@ hipError_t run(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStre
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute((const void *)plain_score<T, D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
     if (e != hipSuccess) return e;
-    plain_window_attention<T, D><<<dim3(a.B * a.Hq), dim3(kThreads), lds1, stream>>>(
-        (const T *)a.q, (const T *)a.k, (const T *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, row_max, row_sum, out,
-        out_rest, rest_frac, top_token);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    if (a.stage_mask & OBC_STAGE_SWEEP1) {      // the plain path has no separate combine stage
+        plain_window_attention<T, D><<<dim3(a.B * a.Hq), dim3(kThreads), lds1, stream>>>(
+            (const T *)a.q, (const T *)a.k, (const T *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, row_max, row_sum,
+            out, out_rest, rest_frac, top_token);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (!(a.stage_mask & OBC_STAGE_SWEEP2)) return hipSuccess;
     const dim3 grid((a.N + kTile - 1) / kTile, a.B * a.Hkv);
     plain_score<T, D><<<grid, dim3(kThreads), lds2, stream>>>(
         (const T *)a.q, (const T *)a.k, (const T *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, a.variant, row_max,
