@@ -396,12 +396,11 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
             }
     }
 
-    const float c2 = kLog2e * kInvSqrtD;
     const float lrow = R.lsum + other_half(R.lsum);
     const size_t prow = ((size_t)bg * n_splits + split) * m_pad + row;
     if (half == 0) {
-        part_ml[prow * 2 + 0] = R.m_raw * c2;    // log2 units; -inf when the split holds no visible key
-        part_ml[prow * 2 + 1] = lrow;
+        part_ml[prow * 4 + 0] = R.m_raw;         // raw q.k units; -inf when the split holds no visible key
+        part_ml[prow * 4 + 1] = lrow;
     }
     if (kNeedO) {
         float *dst = part_o + prow * kD;
@@ -424,7 +423,8 @@ __global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ pa
                                                     int ragged, SeqLens lens, int split_len, int n_splits,
                                                     int m_pad, int need_o, float *__restrict__ row_max,
                                                     float *__restrict__ row_sum, float *__restrict__ out_f32,
-                                                    uint16_t *__restrict__ out_bf16, float *__restrict__ row_const) {
+                                                    uint16_t *__restrict__ out_bf16, float *__restrict__ row_const,
+                                                    float *__restrict__ special) {
     __shared__ float red[2];
     const int row = blockIdx.x, bg = blockIdx.y;
     const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv, M = G * W;
@@ -440,19 +440,22 @@ __global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ pa
             row_const[crow * 4 + 1] = 0.f;
             row_const[crow * 4 + 2] = __int_as_float(-1);
             row_const[crow * 4 + 3] = 0.f;
+            special[crow * 4 + 0] = __int_as_float(-1);
         }
         return;
     }
     const int live_splits = (len + split_len - 1) / split_len;
-    float m = -INFINITY;
-    for (int s = 0; s < live_splits; ++s) m = fmaxf(m, part_ml[(((size_t)bg * n_splits + s) * m_pad + row) * 2]);
+    const float c2 = kLog2e * kInvSqrtD;
+    float m_raw = -INFINITY;                          // max over the row of the raw dot product q.k
+    for (int s = 0; s < live_splits; ++s) m_raw = fmaxf(m_raw, part_ml[(((size_t)bg * n_splits + s) * m_pad + row) * 4]);
     float l = 0.f, o = 0.f;
     for (int s = 0; s < live_splits; ++s) {
         const size_t prow = ((size_t)bg * n_splits + s) * m_pad + row;
-        const float w = exp2f(part_ml[prow * 2] - m);             // 0 for splits hidden from this row
-        l = fmaf(w, part_ml[prow * 2 + 1], l);
+        const float w = exp2f((part_ml[prow * 4] - m_raw) * c2);  // 0 for splits hidden from this row
+        l = fmaf(w, part_ml[prow * 4 + 1], l);
         if (need_o) o = fmaf(w, part_o[prow * kD + dd], o);
     }
+    const float m = m_raw * c2;                       // log2 units
     o = o / l;
     // o^ = hi + lo, the pair of bf16 pieces the second sweep feeds to the matrix cores.
     const uint16_t ob = (uint16_t)(__float_as_uint(o) >> 16);
@@ -474,8 +477,267 @@ __global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ pa
         row_const[crow * 4 + 0] = 2.0f * (m + log2f(l));   // A_ip^2 = exp2(2 log2e Z_ip - this)
         row_const[crow * 4 + 1] = red[0] + red[1];         // ||o^_i||^2
         row_const[crow * 4 + 2] = __int_as_float(len - W + (row % W));
-        row_const[crow * 4 + 3] = 0.f;
+        row_const[crow * 4 + 3] = m_raw;
+        special[crow * 4 + 0] = __int_as_float(-1);        // no separately scored (row, token) pair yet
     }
+}
+
+// ------------------------------------------------------------------------------------
+// Rescue of dominant rows
+// ------------------------------------------------------------------------------------
+// A row whose top key holds almost all of its attention (A_top = 1 / row sum > 0.9; the
+// top is then unique) has o_i ~ v_top, and fp32 sums that contain the top key's weight 1
+// cannot resolve v_top - o_i: the expanded norm loses its last digits near A_top ~ 0.99,
+// so rows are taken out well before that.  Such rows are rare (retrieval-like heads).  They are
+// gathered per KV head and swept once more with the row max known: the top key is left
+// out of the sums, which gives l' = sum_{q != top} exp(z_q - z_top) and O' = sum_{q != top}
+// exp(z_q - z_top) v_q, and then exactly
+//     v_top - o_i = l' / (1 + l') * (v_top - O' / l'),      o_i = v_top - (v_top - o_i).
+// The (row, top key) pair is scored from these in fp32 (`special`), the second sweep skips
+// that pair and adds the stored values, and uses the refreshed o_i for all other keys.
+constexpr float kDominantShare = 0.9f;
+
+// One block per KV head: the dominant rows in row order, then their count.
+__global__ __launch_bounds__(512) void mfma_dominant_list(const float *__restrict__ row_sum, int W, int Hq, int Hkv,
+                                                          int m_pad, int32_t *__restrict__ dom_rows,
+                                                          int32_t *__restrict__ dom_count) {
+    __shared__ int wave_tot[8];
+    const int bg = blockIdx.x, b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv, M = G * W;
+    const int row = threadIdx.x, lane = row & 63, wave = row >> 6;
+    const size_t grow = ((size_t)b * Hq + (size_t)g * G) * W + row;
+    const bool dom = row < M && row_sum[row < M ? grow : 0] * kDominantShare < 1.0f;
+    const unsigned long long bal = __ballot(dom);
+    if (lane == 0) wave_tot[wave] = __popcll(bal);
+    __syncthreads();
+    int before = __popcll(bal & ((1ull << lane) - 1ull)), total = 0;
+    for (int w = 0; w < 8; ++w) {
+        if (w < wave) before += wave_tot[w];
+        total += wave_tot[w];
+    }
+    if (dom) dom_rows[(size_t)bg * m_pad + before] = row;
+    if (row == 0) dom_count[bg] = total;
+}
+
+// Grid: x = sequence split, y = 128-row chunk of the dominant list, z = (b, KV head).
+__global__ __launch_bounds__(kThreads, 2) void mfma_rescue_sweep(const uint16_t *__restrict__ q,
+                                                                 const uint16_t *__restrict__ k,
+                                                                 const uint16_t *__restrict__ v, int N, int W, int Hq,
+                                                                 int Hkv, int ragged, SeqLens lens, int split_len,
+                                                                 int n_splits, int m_pad,
+                                                                 const int32_t *__restrict__ dom_rows,
+                                                                 const int32_t *__restrict__ dom_count,
+                                                                 const float *__restrict__ row_const,
+                                                                 float *__restrict__ part_ml,
+                                                                 float *__restrict__ part_o) {
+    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    const int split = blockIdx.x, chunk = blockIdx.y, bg = blockIdx.z;
+    const int count = dom_count[bg];
+    if (chunk * 128 >= count) return;                            // uniform
+    const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv;
+    const int len = seq_len_of(lens, ragged, b, N);
+    const int t_begin = split * split_len;
+    if (t_begin >= len) return;
+    const int t_end = min(t_begin + split_len, len);
+
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63, half = lane >> 5;
+    const int slot = chunk * 128 + wave * 32 + (lane & 31);      // position in the dominant list
+    const bool wave_active = chunk * 128 + wave * 32 < count;    // uniform
+    const bool row_valid = slot < count;
+    const int row = row_valid ? dom_rows[(size_t)bg * m_pad + slot] : 0;
+    const int vis = row_valid ? len - W + (row % W) : -1;        // unused list slots see nothing
+    const float m_raw = row_const[((size_t)bg * m_pad + row) * 4 + 3];
+    const float c2 = kLog2e * kInvSqrtD, mref = m_raw * c2;
+
+    const char *kh = (const char *)k + (size_t)bg * N * kRowBytes;
+    const char *vh = (const char *)v + (size_t)bg * N * kRowBytes;
+    const uint32_t lds0 = lds_offset_of(smem);
+    int koff[8], voff[4];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) koff[kk] = row_piece_offset(lane, kk);
+#pragma unroll
+    for (int ddb = 0; ddb < 4; ++ddb) voff[ddb] = vt_piece_offset(lane, ddb);
+
+    bf16x8 qreg[8];
+    {
+        const char *qrow = (const char *)q + (((size_t)b * Hq + (size_t)g * G) * W + row) * kRowBytes;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            if (row_valid) qreg[kk] = *(const bf16x8 *)(qrow + (2 * kk + half) * 16);
+            else qreg[kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        }
+    }
+    f32x16 oacc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) oacc[i] = zero16();
+    float lsum = 0.f;
+    int n_top = 0, top_tok = -1;
+
+    const int n_tiles = (t_end - t_begin + kTileTok - 1) / kTileTok;
+    tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane);
+    tile_load_async<kRot4>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane);
+    for (int it = 0; it < n_tiles; ++it) {
+        wait_async_loads();
+        __syncthreads();            // tile `it` is in LDS; everyone is done with the other slots
+        if (it + 1 < n_tiles) {
+            tile_load_async<kXor16>(kh, t_begin + (it + 1) * kTileTok, len - 1, lds0 + (((it + 1) & 1) ? kLdsK1 : kLdsK0), wave, lane);
+            tile_load_async<kRot4>(vh, t_begin + (it + 1) * kTileTok, len - 1, lds0 + (((it + 1) & 1) ? kLdsV1 : kLdsV0), wave, lane);
+        }
+        if (!wave_active) continue;
+        const char *ktile = smem + ((it & 1) ? kLdsK1 : kLdsK0);
+        const char *vtile = smem + ((it & 1) ? kLdsV1 : kLdsV0);
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            // Same operands, same order as sweep 1: the raw dot products repeat bit for bit,
+            // so the top key is the one whose value equals the stored row max.
+            f32x16 s = zero16();
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) {
+                const bf16x8 a = lds_read16(ktile + tb * 32 * kRowBytes + koff[kk]);
+                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[kk], s, 0, 0, 0);
+            }
+            const int tok0 = t_begin + it * kTileTok + tb * 32;
+            float p[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int tok = tok0 + 8 * (r >> 2) + 4 * half + (r & 3);
+                const bool seen = tok <= vis && tok < t_end;
+                const bool top = seen && s[r] == m_raw;
+                p[r] = (seen && !top) ? __builtin_amdgcn_exp2f(fmaf(s[r], c2, -mref)) : 0.f;
+                lsum += p[r];
+                if (top) { ++n_top; top_tok = tok; }
+            }
+            PiecePair phi[2], plo[2];
+#pragma unroll
+            for (int sx = 0; sx < 2; ++sx)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float p0 = p[8 * sx + 2 * e], p1 = p[8 * sx + 2 * e + 1];
+                    const uint32_t h0 = __float_as_uint(p0) & 0xffff0000u, h1 = __float_as_uint(p1) & 0xffff0000u;
+                    phi[sx].u[e] = __builtin_amdgcn_perm(h1, h0, 0x07060302u);
+                    plo[sx].u[e] = pack_bf16(p0 - __uint_as_float(h0), p1 - __uint_as_float(h1));
+                }
+#pragma unroll
+            for (int ddb = 0; ddb < 4; ++ddb)
+#pragma unroll
+                for (int sx = 0; sx < 2; ++sx) {
+                    const bf16x8 a = lds_read_vt(vtile + (tb * 32 + 16 * sx) * kRowBytes + voff[ddb]);
+                    oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, phi[sx].v, oacc[ddb], 0, 0, 0);
+                    oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, plo[sx].v, oacc[ddb], 0, 0, 0);
+                }
+        }
+    }
+    if (!wave_active) return;
+    const float lrow = lsum + other_half(lsum);
+    const int n_top_row = n_top + __shfl_xor(n_top, 32);
+    const int top_tok_row = max(top_tok, __shfl_xor(top_tok, 32));
+    const size_t prow = ((size_t)bg * n_splits + split) * m_pad + slot;     // indexed by list position
+    if (half == 0) {
+        part_ml[prow * 4 + 0] = lrow;
+        part_ml[prow * 4 + 1] = (float)n_top_row;
+        part_ml[prow * 4 + 2] = __int_as_float(top_tok_row);
+    }
+    float *dst = part_o + prow * kD;
+#pragma unroll
+    for (int ddb = 0; ddb < 4; ++ddb)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const int dd = ddb * 32 + 8 * r4 + 4 * half;
+            *(float4 *)(dst + dd) = make_float4(oacc[ddb][4 * r4], oacc[ddb][4 * r4 + 1], oacc[ddb][4 * r4 + 2],
+                                                oacc[ddb][4 * r4 + 3]);
+        }
+}
+
+// One 128-thread block per (list position, KV head); thread = head_dim element.
+__global__ __launch_bounds__(128) void mfma_rescue_combine(const uint16_t *__restrict__ v,
+                                                           const float *__restrict__ part_ml,
+                                                           const float *__restrict__ part_o, int N, int W, int Hq,
+                                                           int Hkv, int ragged, SeqLens lens, int split_len,
+                                                           int n_splits, int m_pad,
+                                                           const int32_t *__restrict__ dom_rows,
+                                                           const int32_t *__restrict__ dom_count,
+                                                           float *__restrict__ row_sum, float *__restrict__ out_f32,
+                                                           uint16_t *__restrict__ out_bf16,
+                                                           float *__restrict__ row_const,
+                                                           float *__restrict__ special) {
+    __shared__ float red[4][2];
+    const int slot = blockIdx.x, bg = blockIdx.y;
+    if (slot >= dom_count[bg]) return;
+    const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv;
+    const int len = seq_len_of(lens, ragged, b, N);
+    const int row = dom_rows[(size_t)bg * m_pad + slot];
+    const int dd = threadIdx.x;
+    const int live_splits = (len + split_len - 1) / split_len;
+    float lrest = 0.f, orest = 0.f, n_top = 0.f;
+    int top_tok = -1;
+    for (int s = 0; s < live_splits; ++s) {
+        const size_t prow = ((size_t)bg * n_splits + s) * m_pad + slot;
+        lrest += part_ml[prow * 4 + 0];
+        n_top += part_ml[prow * 4 + 1];
+        top_tok = max(top_tok, __float_as_int(part_ml[prow * 4 + 2]));
+        orest += part_o[prow * kD + dd];
+    }
+    if (n_top != 1.0f || top_tok < 0) return;       // cannot happen for a row above kDominantShare; keep the plain results
+    const size_t crow = (size_t)bg * m_pad + row;
+    const size_t lo_plane = (size_t)gridDim.y * m_pad * kD;
+    const float vt = bf16_bits_to_float(v[((size_t)bg * N + top_tok) * kD + dd]);
+    const float ltot = 1.0f + lrest;                 // the top key's own weight is exp(0) = 1
+    const float frac = lrest / ltot;                 // 1 - A_top
+    const float rest = lrest > 0.f ? orest / lrest : 0.f;
+    const float diff = frac * (vt - rest);           // (v_top - o_i)[dd]
+    const float o = vt - diff;
+    const float m_raw = row_const[crow * 4 + 3];
+    const float z = m_raw * kInvSqrtD;               // Z of the (row, top key) pair
+    const float comb = fmaf(z, diff, vt);            // ((1+Z) v_top - Z o_i)[dd]
+    const uint16_t ob = (uint16_t)(__float_as_uint(o) >> 16);
+    const float ohi = bf16_bits_to_float(ob);
+    const uint16_t olo = (uint16_t)(pack_bf16(o - ohi, 0.f) & 0xffffu);
+    const float of = ohi + bf16_bits_to_float(olo);
+    float sums[4] = {of * of, vt * vt, diff * diff, comb * comb};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) sums[c] += __shfl_xor(sums[c], off);
+        if ((dd & 63) == 0) red[c][dd >> 6] = sums[c];
+    }
+    __syncthreads();
+    const size_t grow = ((size_t)b * Hq + (size_t)g * G) * W + row;
+    out_f32[grow * kD + dd] = o;
+    out_bf16[crow * kD + dd] = ob;
+    out_bf16[lo_plane + crow * kD + dd] = olo;
+    if (dd == 0) {
+        const float a = 1.0f / ltot, a2 = a * a;
+        row_sum[grow] = ltot;
+        row_const[crow * 4 + 0] = 2.0f * (m_raw * (kLog2e * kInvSqrtD) + log2f(ltot));
+        row_const[crow * 4 + 1] = red[0][0] + red[0][1];
+        special[crow * 4 + 0] = __int_as_float(top_tok);
+        special[crow * 4 + 1] = a2 * (red[1][0] + red[1][1]);                 // Eq. 4 term of the pair
+        special[crow * 4 + 2] = a2 * z * z * (red[2][0] + red[2][1]);         // Eq. 5 term
+        special[crow * 4 + 3] = a2 * (red[3][0] + red[3][1]);                 // Eq. 6 term (completed square)
+    }
+}
+
+hipError_t launch_rescue(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStream_t stream) {
+    const int BH = a.B * a.Hkv;
+    int32_t *dom_rows = (int32_t *)(base + ws.dom_rows);
+    int32_t *dom_count = dom_rows + (size_t)BH * ws.m_pad;
+    float *part_ml = (float *)(base + ws.part_ml), *part_o = (float *)(base + ws.part_o);
+    mfma_dominant_list<<<dim3(BH), dim3(512), 0, stream>>>((const float *)(base + ws.row_sum), a.W, a.Hq, a.Hkv,
+                                                           ws.m_pad, dom_rows, dom_count);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void *)mfma_rescue_sweep, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTiles);
+    if (e != hipSuccess) return e;
+    mfma_rescue_sweep<<<dim3(ws.splits, ws.n_chunks, BH), dim3(kThreads), kLdsTiles, stream>>>(
+        (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens,
+        ws.split_len, ws.splits, ws.m_pad, dom_rows, dom_count, (const float *)(base + ws.row_const), part_ml, part_o);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    mfma_rescue_combine<<<dim3(ws.m_pad, BH), dim3(128), 0, stream>>>(
+        (const uint16_t *)a.v, part_ml, part_o, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, ws.split_len, ws.splits,
+        ws.m_pad, dom_rows, dom_count, (float *)(base + ws.row_sum), (float *)(base + ws.out_f32),
+        (uint16_t *)(base + ws.out_bf16), (float *)(base + ws.row_const), (float *)(base + ws.special));
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------
@@ -493,105 +755,96 @@ __device__ __forceinline__ float sumsq8(const bf16x8 x, float acc) {
 struct Sweep2Regs {
     bf16x8 q[8], ohi[8], olo[8];   // stationary A operands of this wave's row block
     float c_m2[16], c_oo[16];      // per accumulator register: 2 (max + log2 sum), ||o^||^2 of its row
-    f32x16 z_cur, vo_cur;          // raw q.k and o^.v of the block whose scores are due
-    float vv_cur;                  // this lane's half of ||v||^2 of its token in that block
 };
 
-// One pipeline step n of sweep 2 (PH = n mod 4 fixes the LDS slots):
-//   matrix cores: Z = Q K^T and O V^T of block n+1 (+ ||v||^2 on the dot-product unit)
-//   vector ALUs : scores of block n, summed over this wave's 32 rows, parked in LDS
+// One step of sweep 2 = one block of 32 tokens (PH = n mod 4 fixes the LDS slot):
+//   matrix cores: Z = Q K^T and O V^T of the block (+ ||v||^2 on the dot-product unit)
+//   vector ALUs : its scores, summed over this wave's 32 rows, parked in LDS
+// The two phases of one wave do not overlap; the second wave on the SIMD runs in the gaps
+// (on this hardware a 32x32x16 matrix op blocks most vector-ALU issue anyway).
+// Even steps first wait for the tile issued two steps earlier and start the next one.
 template <int PH, bool kMasked, int kVariant>
 __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uint32_t lds0, int n, int n_blk,
-                                            int t_begin, int t_end, int last_row, const int *vis_i, const char *kh,
-                                            const char *vh, const int (&koff)[8], int wave, int lane,
-                                            bool wave_active, float *plane_w) {
+                                            int t_begin, int t_end, int last_row, const int *vis_i,
+                                            const int *excl_i, const char *kh, const char *vh,
+                                            const int (&koff)[8], int wave, int lane, bool wave_active,
+                                            float *plane_w) {
     constexpr int kNv = kVariant == OBC_ALL ? 3 : 1;
     constexpr bool kDoV = kVariant == OBC_VALUE || kVariant == OBC_ALL;
     constexpr bool kDoK = kVariant == OBC_KEY || kVariant == OBC_ALL;
     constexpr bool kDoJ = kVariant == OBC_JOINT || kVariant == OBC_ALL;
     constexpr bool kNeedVO = kDoK || kDoJ;
-    constexpr int kSlot = (PH == 0 || PH == 3) ? 0 : 1;               // tile of block n+1
-    constexpr int kBlk = (PH == 0 || PH == 2) ? 1 : 0;
+    constexpr int kSlot = PH >> 1, kBlk = PH & 1;
     constexpr int kKBase = (kSlot ? kLdsK1 : kLdsK0) + kBlk * 32 * kRowBytes;
     constexpr int kVBase = (kSlot ? kLdsV1 : kLdsV0) + kBlk * 32 * kRowBytes;
     const int half = lane >> 5;
     const float c2x2 = 2.0f * kLog2e * kInvSqrtD;
 
-    if (PH & 1) {
+    if ((PH & 1) == 0) {
         wait_async_loads();
         __syncthreads();
-        const int tn = t_begin + (((n + 1) >> 1) + 1) * kTileTok;     // first token of the tile to start now
+        const int tn = t_begin + ((n >> 1) + 1) * kTileTok;           // first token of the tile to start now
         if (tn < t_end) {
-            tile_load_async<kXor16>(kh, tn, last_row, lds0 + (PH == 1 ? kLdsK0 : kLdsK1), wave, lane);
-            tile_load_async<kXor16>(vh, tn, last_row, lds0 + (PH == 1 ? kLdsV0 : kLdsV1), wave, lane);
+            tile_load_async<kXor16>(kh, tn, last_row, lds0 + (PH == 0 ? kLdsK1 : kLdsK0), wave, lane);
+            tile_load_async<kXor16>(vh, tn, last_row, lds0 + (PH == 0 ? kLdsV1 : kLdsV0), wave, lane);
         }
     }
-    if (!wave_active) {
-        if (half == 0 && n < n_blk) {
-#pragma unroll
-            for (int c = 0; c < kNv; ++c) plane_w[(n * 32 + lane) * kNv + c] = 0.f;
-        }
-        return;
-    }
-
-    // ---- matrix cores: block n+1 ----
-    f32x16 z_next = zero16(), vo_next = zero16();
-    float vv_next = 0.f;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-        const bf16x8 kb = lds_read16(smem + kKBase + koff[kk]);
-        z_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.q[kk], kb, z_next, 0, 0, 0);
-    }
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-        const bf16x8 vb = lds_read16(smem + kVBase + koff[kk]);
-        vv_next = sumsq8(vb, vv_next);
-        if (kNeedVO) {
-            vo_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.ohi[kk], vb, vo_next, 0, 0, 0);
-            vo_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.olo[kk], vb, vo_next, 0, 0, 0);
-        }
-    }
-
-    // ---- vector ALUs: block n ----
-    const float vv = R.vv_cur + other_half(R.vv_cur);          // ||v_p||^2 of this lane's token
-    const int tok = t_begin + n * 32 + (lane & 31);
+    if (n >= n_blk) return;                                            // uniform
     float acc_v = 0.f, acc_k = 0.f, acc_j = 0.f;
+    if (wave_active) {
+        // ---- matrix cores ----
+        f32x16 z = zero16(), vo = zero16();
+        float vv = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        float a2 = __builtin_amdgcn_exp2f(fmaf(R.z_cur[r], c2x2, -R.c_m2[r]));   // A_ip^2
-        if (kMasked) {
-            const int i = wave * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-            if (tok > vis_i[i] || tok >= t_end) a2 = 0.f;
+        for (int kk = 0; kk < 8; ++kk) {
+            const bf16x8 kb = lds_read16(smem + kKBase + koff[kk]);
+            z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.q[kk], kb, z, 0, 0, 0);
         }
-        const float zz = R.z_cur[r] * kInvSqrtD;                                  // Z_ip
-        if (kDoV) acc_v += a2;
-        if (kDoK) {
-            const float nrm = fmaf(R.vo_cur[r], -2.0f, vv + R.c_oo[r]);           // ||v_p - o^_i||^2
-            acc_k = fmaf(a2 * zz * zz, fmaxf(nrm, 0.f), acc_k);
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) {
+            const bf16x8 vb = lds_read16(smem + kVBase + koff[kk]);
+            vv = sumsq8(vb, vv);
+            if (kNeedVO) {
+                vo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.ohi[kk], vb, vo, 0, 0, 0);
+                vo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.olo[kk], vb, vo, 0, 0, 0);
+            }
         }
-        if (kDoJ) {
-            // ||(1+Z) v - Z o^||^2 = (1+Z)^2 ||v||^2 - 2 Z (1+Z) v.o^ + Z^2 ||o^||^2
-            const float y = zz + 1.0f;
-            const float t1 = zz * R.vo_cur[r];
-            const float t2 = fmaf(t1, -2.0f, y * vv);
-            const float t3 = fmaf(zz * R.c_oo[r], zz, y * t2);
-            acc_j = fmaf(a2, fmaxf(t3, 0.f), acc_j);
+        vv += other_half(vv);                                          // ||v_p||^2 of this lane's token
+        // ---- vector ALUs ----
+        const int tok = t_begin + n * 32 + (lane & 31);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            float a2 = __builtin_amdgcn_exp2f(fmaf(z[r], c2x2, -R.c_m2[r]));      // A_ip^2
+            if (kMasked) {
+                const int i = wave * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (tok > vis_i[i] || tok >= t_end || tok == excl_i[i]) a2 = 0.f; // hidden, padded, or scored separately
+            }
+            const float zz = z[r] * kInvSqrtD;                                    // Z_ip
+            if (kDoV) acc_v += a2;
+            if (kDoK) {
+                const float nrm = fmaf(vo[r], -2.0f, vv + R.c_oo[r]);             // ||v_p - o^_i||^2
+                acc_k = fmaf(a2 * zz * zz, fmaxf(nrm, 0.f), acc_k);
+            }
+            if (kDoJ) {
+                // ||(1+Z) v - Z o^||^2 = (1+Z)^2 ||v||^2 - 2 Z (1+Z) v.o^ + Z^2 ||o^||^2
+                const float y = zz + 1.0f;
+                const float t1 = zz * vo[r];
+                const float t2 = fmaf(t1, -2.0f, y * vv);
+                const float t3 = fmaf(zz * R.c_oo[r], zz, y * t2);
+                acc_j = fmaf(a2, fmaxf(t3, 0.f), acc_j);
+            }
         }
+        if (kDoV) { acc_v *= vv; acc_v += other_half(acc_v); }
+        if (kDoK) acc_k += other_half(acc_k);
+        if (kDoJ) acc_j += other_half(acc_j);
     }
-    if (kDoV) { acc_v *= vv; acc_v += other_half(acc_v); }
-    if (kDoK) acc_k += other_half(acc_k);
-    if (kDoJ) acc_j += other_half(acc_j);
-    if (half == 0 && n < n_blk) {
+    if (half == 0) {
         float *pw = plane_w + (n * 32 + lane) * kNv;
         int c = 0;
         if (kDoV) pw[c++] = acc_v;
         if (kDoK) pw[c++] = acc_k;
         if (kDoJ) pw[c++] = acc_j;
     }
-    R.z_cur = z_next;
-    R.vo_cur = vo_next;
-    R.vv_cur = vv_next;
-    interleave_hint<kNeedVO ? 24 : 8, kNeedVO ? 10 : 12, 1>();
 }
 
 // kVariant: OBC_VALUE / OBC_KEY / OBC_JOINT / OBC_ALL.  Grid: x = token range, y = chunk, z = (b, KV head).
@@ -604,13 +857,15 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
                                                            int Hkv, int ragged, SeqLens lens, int range_len, int m_pad,
                                                            const uint16_t *__restrict__ out_bf16,
                                                            const float *__restrict__ row_const,
+                                                           const float *__restrict__ special,
                                                            float *__restrict__ dst, size_t variant_stride,
                                                            size_t chunk_stride) {
     constexpr int kNv = kVariant == OBC_ALL ? 3 : 1;
     constexpr bool kNeedVO = kVariant != OBC_VALUE;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     float *vis_s = (float *)(smem + kLdsTiles);                // [128] last visible key of each row of the chunk
-    float *plane = vis_s + 128;                                // [4 waves][range_len][kNv]
+    float *excl_s = vis_s + 128;                               // [128] key of the row that is scored separately, or -1
+    float *plane = excl_s + 128;                               // [4 waves][range_len][kNv]
 
     const int range = blockIdx.x, chunk = blockIdx.y, bg = blockIdx.z;
     const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv, M = G * W;
@@ -658,12 +913,12 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
         }
     }
     // Constants of the 16 rows this lane meets in the accumulators: row rb*32 + 8 (r/4) + 4 half + r%4.
-    int vis_min = 0x7fffffff;
+    int vis_min = 0x7fffffff;                                  // first key some row of this wave cannot see
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int i = rb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
         const bool ok = wave_active && i < m_pad;
-        R.c_m2[r] = ok ? row_const[(cbase + i) * 4 + 0] : 1e30f;
+        R.c_m2[r] = ok ? row_const[(cbase + i) * 4 + 0] : 1e30f;      // padded rows weigh nothing
         R.c_oo[r] = ok ? row_const[(cbase + i) * 4 + 1] : 0.f;
         const int vi = ok ? __float_as_int(row_const[(cbase + i) * 4 + 2]) : -1;
         if (vi >= 0) vis_min = min(vis_min, vi);
@@ -677,47 +932,28 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) { settle(R.c_m2[r]); settle(R.c_oo[r]); }
+    int mine_special = 0;
     if (threadIdx.x < 128) {
         const int i = chunk * 128 + threadIdx.x;
         vis_s[threadIdx.x] = i < m_pad ? row_const[(cbase + i) * 4 + 2] : __int_as_float(-1);
+        const int ex = (kNeedVO && i < m_pad) ? __float_as_int(special[(cbase + i) * 4 + 0]) : -1;
+        excl_s[threadIdx.x] = __int_as_float(ex);
+        mine_special = ex >= t_begin && ex < t_end;
     }
-    const int *vis_i = (const int *)vis_s;
+    const int *vis_i = (const int *)vis_s, *excl_i = (const int *)excl_s;
     float *plane_w = plane + (size_t)wave * range_len * kNv;
+    // Uniform: some (row, key) pair of this chunk and token range is scored separately.
+    const bool has_special = __syncthreads_or(mine_special) != 0;
 
-    // Prologue: tile 0, then block 0's contractions.
+    // Tile 0 is started here; step 0 waits for it.
     tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane);
     tile_load_async<kXor16>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane);
-    wait_async_loads();
-    __syncthreads();
-    if (t_begin + kTileTok < t_end) {
-        tile_load_async<kXor16>(kh, t_begin + kTileTok, len - 1, lds0 + kLdsK1, wave, lane);
-        tile_load_async<kXor16>(vh, t_begin + kTileTok, len - 1, lds0 + kLdsV1, wave, lane);
-    }
-    R.z_cur = zero16();
-    R.vo_cur = zero16();
-    R.vv_cur = 0.f;
-    if (wave_active) {
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            const bf16x8 kb = lds_read16(smem + kLdsK0 + koff[kk]);
-            R.z_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.q[kk], kb, R.z_cur, 0, 0, 0);
-        }
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            const bf16x8 vb = lds_read16(smem + kLdsV0 + koff[kk]);
-            R.vv_cur = sumsq8(vb, R.vv_cur);
-            if (kNeedVO) {
-                R.vo_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.ohi[kk], vb, R.vo_cur, 0, 0, 0);
-                R.vo_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.olo[kk], vb, R.vo_cur, 0, 0, 0);
-            }
-        }
-    }
 
     const int n_blk = (t_end - t_begin + 31) / 32;
     const int n_total = (n_blk + 3) & ~3;
     int n_plain = (vis_min + 1 - t_begin) / 32;
-    n_plain = max(0, min(n_plain, n_blk)) & ~3;
-#define OBC_S2_ARGS smem, lds0, n, n_blk, t_begin, t_end, len - 1, vis_i, kh, vh, koff, wave, lane, wave_active, plane_w
+    n_plain = has_special ? 0 : (max(0, min(n_plain, n_blk)) & ~3);
+#define OBC_S2_ARGS smem, lds0, n, n_blk, t_begin, t_end, len - 1, vis_i, excl_i, kh, vh, koff, wave, lane, wave_active, plane_w
     int n = 0;
     for (; n < n_plain; n += 4) {
         sweep2_step<0, false, kVariant>(R, OBC_S2_ARGS); ++n;
@@ -744,6 +980,20 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
             out[c * variant_stride + t_begin + t] = s;
         }
     }
+    if (has_special) {      // add the separately scored pairs, in row order, by one thread
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int i = 0; i < 128; ++i) {
+                const int ex = excl_i[i];
+                if (ex < t_begin || ex >= t_end) continue;
+                const float *sp = special + (cbase + chunk * 128 + i) * 4;
+                int c = 0;
+                if (kVariant == OBC_VALUE || kVariant == OBC_ALL) out[(c++) * variant_stride + ex] += sp[1];
+                if (kVariant == OBC_KEY || kVariant == OBC_ALL) out[(c++) * variant_stride + ex] += sp[2];
+                if (kVariant == OBC_JOINT || kVariant == OBC_ALL) out[(c++) * variant_stride + ex] += sp[3];
+            }
+        }
+    }
 }
 
 // scores[c][idx] = sum over chunks of planes[chunk][c][idx], in chunk order.
@@ -759,7 +1009,7 @@ __global__ __launch_bounds__(256) void mfma_sum_planes(const float *__restrict__
 template <int kVariant>
 hipError_t launch_sweep2(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStream_t stream) {
     constexpr int nv = kVariant == OBC_ALL ? 3 : 1;
-    const size_t lds = kLdsTiles + 128 * sizeof(float) + (size_t)4 * ws.range_len * nv * sizeof(float);
+    const size_t lds = kLdsTiles + 256 * sizeof(float) + (size_t)4 * ws.range_len * nv * sizeof(float);
     hipError_t e = hipFuncSetAttribute((const void *)mfma_sweep2<kVariant>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     const size_t plane_elems = (size_t)a.B * a.Hkv * a.N;
@@ -768,8 +1018,8 @@ hipError_t launch_sweep2(const ScoreArgs &a, const ScoreWorkspace &ws, char *bas
     const dim3 grid((a.N + ws.range_len - 1) / ws.range_len, ws.n_chunks, a.B * a.Hkv);
     mfma_sweep2<kVariant><<<grid, dim3(kThreads), lds, stream>>>(
         (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens,
-        ws.range_len, ws.m_pad, (const uint16_t *)(base + ws.out_bf16), (const float *)(base + ws.row_const), dst,
-        plane_elems, chunk_stride);
+        ws.range_len, ws.m_pad, (const uint16_t *)(base + ws.out_bf16), (const float *)(base + ws.row_const),
+        (const float *)(base + ws.special), dst, plane_elems, chunk_stride);
     e = hipGetLastError();
     if (e != hipSuccess || ws.n_chunks == 1) return e;
     const size_t total = plane_elems * nv;
@@ -793,7 +1043,9 @@ void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWo
     const size_t rows = (size_t)BH * ws->m_pad;
     ws->out_bf16 = *off;  *off = align_up(*off + 2 * rows * d * 2, 256);   // high pieces, then residual pieces
     ws->row_const = *off; *off = align_up(*off + rows * 4 * sizeof(float), 256);
-    ws->part_ml = *off;   *off = align_up(*off + rows * ws->splits * 2 * sizeof(float), 256);
+    ws->part_ml = *off;   *off = align_up(*off + rows * ws->splits * 4 * sizeof(float), 256);
+    ws->special = *off;   *off = align_up(*off + rows * 4 * sizeof(float), 256);
+    ws->dom_rows = *off;  *off = align_up(*off + (rows + BH) * sizeof(int32_t), 256);
     ws->part_o = *off;    *off = align_up(*off + rows * ws->splits * d * sizeof(float), 256);
     ws->planes = *off;
     if (ws->n_chunks > 1) *off = align_up(*off + (size_t)ws->n_chunks * nv * BH * N * sizeof(float), 256);
@@ -824,9 +1076,14 @@ hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char 
         mfma_combine<<<dim3(ws.m_pad, a.B * a.Hkv), dim3(128), 0, stream>>>(
             part_ml, part_o, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, ws.split_len, ws.splits, ws.m_pad,
             need_o ? 1 : 0, (float *)(base + ws.row_max), (float *)(base + ws.row_sum),
-            (float *)(base + ws.out_f32), (uint16_t *)(base + ws.out_bf16), (float *)(base + ws.row_const));
+            (float *)(base + ws.out_f32), (uint16_t *)(base + ws.out_bf16), (float *)(base + ws.row_const),
+            (float *)(base + ws.special));
         e = hipGetLastError();
         if (e != hipSuccess) return e;
+        if (need_o) {
+            e = launch_rescue(a, ws, base, stream);
+            if (e != hipSuccess) return e;
+        }
     }
     if (!(a.stage_mask & OBC_STAGE_SWEEP2)) return hipSuccess;
     switch (a.variant) {

@@ -35,9 +35,13 @@ def _run_case(wl):
         assert np.isfinite(gpu).all() and (gpu >= 0).all(), name
         worst[name], where = score_error(gpu, ref[vi], wl.budget, lens, tol)
         assert worst[name] <= tol, "%s %s: err %.3g at %s" % (wl.name, name, worst[name], where)
-        # single-variant calls give the same bits as the all-variant call
+        # single-variant calls agree with the all-variant call (the value-only call skips the
+        # attention outputs, and with them the refinement of dominant rows, so bits may differ)
         one = obc.obc_score(dev["q"], dev["k"], dev["v"], name, seq_lens=lens)
-        assert torch.equal(one, all3[vi]), name
+        if name == "value":
+            torch.testing.assert_close(one, all3[vi], rtol=2e-5, atol=0.0)
+        else:
+            assert torch.equal(one, all3[vi]), name
         # selection: bit-exact vs the oracle's select on the very same fp32 scores
         keep = obc.obc_select(all3[vi].contiguous(), wl.budget, seq_lens=lens)
         keep_np = keep.cpu().numpy()
