@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--variant", default="joint")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-heads", type=int, default=8, help="KV heads of sequence 0 the oracle is timed on")
+    ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = the whole batch)")
     return ap.parse_args()
 
 
@@ -142,20 +142,22 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         x = synth.make_inputs(wl, layer=0)
-        G = Hq // Hkv
-        nh = min(args.cpu_heads, Hkv)
-        L0 = lens[0] if lens else N
-        qs, ks, vs = x["q"][0:1, : nh * G], x["k"][0:1, :nh], x["v"][0:1, :nh]
+        nb = B if args.cpu_seqs <= 0 else min(args.cpu_seqs, B)
+        sub_lens = lens[:nb] if lens else None
         c0 = time.perf_counter()
-        s = oracle.score(qs, ks, vs, seq_lens=[L0] if lens else None)
-        keep_ref = oracle.select(s[2].astype("float32"), wl.budget, [L0] if lens else None)
+        s = oracle.score(x["q"][:nb], x["k"][:nb], x["v"][:nb], seq_lens=sub_lens)
+        keep_ref = oracle.select(s[2].astype("float32"), wl.budget, sub_lens)
+        kb, vb = (x[t][:nb].view(torch.int16).numpy() for t in ("k", "v")) if wl.dtype == "bf16" else \
+                 (x[t][:nb].numpy() for t in ("k", "v"))
+        oracle.compact(kb, vb, keep_ref)
         c1 = time.perf_counter()
-        frac_heads = nh / Hkv
+        cpu_tokens = sum(sub_lens) if sub_lens else nb * N
         cpu = {
-            "value": round(L0 * frac_heads / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+            "value": round(cpu_tokens / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.num_threads(),
             "kind": "oracle",
-            "sample": "sequence 0, %d of %d KV heads (%d head-tokens), fp64 score (3 variants) + select; %.1f s"
-                      % (nh, Hkv, L0 * nh, c1 - c0),
+            "sample": "%d of %d sequences, all %d KV heads (%d head-tokens): fp64 score (3 variants) + select + "
+                      "compact, %.1f s wall on %d threads" % (nb, B, Hkv, cpu_tokens * Hkv, c1 - c0,
+                                                             oracle.num_threads()),
         }
         del keep_ref
 

@@ -78,15 +78,36 @@ __device__ __forceinline__ uint32_t lds_offset_of(const void *p) {
 __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_off) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_off), "v"(gptr) : "memory");
 }
+// Same transfer with the address split into a wave-uniform 64-bit base (scalar registers)
+// and a per-lane 32-bit byte offset: no vector-ALU address arithmetic per transfer.
+__device__ __forceinline__ void dma16_based(const void *sbase, uint32_t voff, uint32_t lds_off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_off), "v"(voff), "s"(sbase) : "memory");
+}
 __device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // Asynchronous copy of one 64-row tile.  Each wave issues four transfers; lane l of
 // transfer n lands at row 4 (4 wave + n) + l / 16, slot l % 16, and picks the global piece
 // that belongs in that slot.  Rows past `last_row` re-read `last_row` (memory beyond the
 // true length is never touched).
+// Per-lane byte offsets of the four transfers inside a tile whose 64 rows all exist.
+template <int SWZ>
+__device__ __forceinline__ void tile_lane_offsets(uint32_t (&doff)[4], int wave, int lane) {
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+        const int R = (wave * 4 + n) * 4 + (lane >> 4);
+        doff[n] = (uint32_t)(R * kRowBytes + piece_of(SWZ, R, lane & 15) * 16);
+    }
+}
+
 template <int SWZ>
 __device__ __forceinline__ void tile_load_async(const char *__restrict__ head_base, int t0, int last_row,
-                                                uint32_t lds_tile, int wave, int lane) {
+                                                uint32_t lds_tile, int wave, int lane, const uint32_t (&doff)[4]) {
+    if (t0 + kTileTok - 1 <= last_row) {            // uniform: the common case, every row of the tile exists
+        const char *sbase = head_base + (size_t)t0 * kRowBytes;
+#pragma unroll
+        for (int n = 0; n < 4; ++n) dma16_based(sbase, doff[n], lds_tile + (wave * 4 + n) * 1024);
+        return;
+    }
 #pragma unroll
     for (int n = 0; n < 4; ++n) {
         const int R = (wave * 4 + n) * 4 + (lane >> 4);
@@ -183,8 +204,8 @@ struct Sweep1Regs {
 template <int PH, bool kMasked, bool kNeedO>
 __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uint32_t lds0, int n, int t_begin,
                                             int t_end, int last_row, int vis, const char *kh, const char *vh,
-                                            const int (&koff)[8], const int (&voff)[4], int wave, int lane,
-                                            bool wave_active) {
+                                            const int (&koff)[8], const int (&voff)[4], const uint32_t (&kdoff)[4],
+                                            const uint32_t (&vdoff)[4], int wave, int lane, bool wave_active) {
     constexpr int kKSlot = (PH == 0 || PH == 3) ? kLdsK0 : kLdsK1;      // tile of block n+1
     constexpr int kKBlk = (PH == 0 || PH == 2) ? 1 : 0;
     constexpr int kVSlot = (PH == 1 || PH == 2) ? kLdsV0 : kLdsV1;      // tile of block n-1
@@ -197,8 +218,8 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
         __syncthreads();
         const int t = (n + 1) >> 1;                     // this step starts K tile t+1 and V tile t
         const int tk = t_begin + (t + 1) * kTileTok, tv = t_begin + t * kTileTok;
-        if (tk < t_end) tile_load_async<kXor16>(kh, tk, last_row, lds0 + (PH == 1 ? kLdsK0 : kLdsK1), wave, lane);
-        if (kNeedO && tv < t_end) tile_load_async<kRot4>(vh, tv, last_row, lds0 + (PH == 1 ? kLdsV1 : kLdsV0), wave, lane);
+        if (tk < t_end) tile_load_async<kXor16>(kh, tk, last_row, lds0 + (PH == 1 ? kLdsK0 : kLdsK1), wave, lane, kdoff);
+        if (kNeedO && tv < t_end) tile_load_async<kRot4>(vh, tv, last_row, lds0 + (PH == 1 ? kLdsV1 : kLdsV0), wave, lane, vdoff);
     }
     if (!wave_active) return;
     // The running max moved in the previous step: bring the accumulated O^T (blocks <= n-2)
@@ -344,12 +365,15 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
 
     // Prologue: the step before block 0 multiplies zero weights with whatever the second V
     // tile holds, so that tile is cleared; K tile 0 is fetched and block 0's S^T formed.
+    uint32_t kdoff[4], vdoff[4];
+    tile_lane_offsets<kXor16>(kdoff, wave, lane);
+    tile_lane_offsets<kRot4>(vdoff, wave, lane);
     for (int e = threadIdx.x; e < kTileBytes / 16; e += kThreads) ((uint4 *)(smem + kLdsV1))[e] = make_uint4(0, 0, 0, 0);
-    tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane);
+    tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane, kdoff);
     wait_async_loads();
     __syncthreads();
-    if (t_begin + kTileTok < t_end) tile_load_async<kXor16>(kh, t_begin + kTileTok, len - 1, lds0 + kLdsK1, wave, lane);
-    if (kNeedO) tile_load_async<kRot4>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane);
+    if (t_begin + kTileTok < t_end) tile_load_async<kXor16>(kh, t_begin + kTileTok, len - 1, lds0 + kLdsK1, wave, lane, kdoff);
+    if (kNeedO) tile_load_async<kRot4>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane, vdoff);
     R.s_cur = zero16();
     if (wave_active) {
 #pragma unroll
@@ -363,7 +387,7 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
     const int n_total = (n_blk + 3) & ~3;
     int n_plain = (vis_min + 1 - t_begin) / 32;       // leading blocks every row of this wave sees in full
     n_plain = max(0, min(n_plain, n_blk)) & ~3;
-#define OBC_S1_ARGS smem, lds0, n, t_begin, t_end, len - 1, vis, kh, vh, koff, voff, wave, lane, wave_active
+#define OBC_S1_ARGS smem, lds0, n, t_begin, t_end, len - 1, vis, kh, vh, koff, voff, kdoff, vdoff, wave, lane, wave_active
     int n = 0;
     for (; n < n_plain; n += 4) {
         sweep1_step<0, false, kNeedO>(R, OBC_S1_ARGS); ++n;
@@ -574,14 +598,17 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_rescue_sweep(const uint16_t 
     int n_top = 0, top_tok = -1;
 
     const int n_tiles = (t_end - t_begin + kTileTok - 1) / kTileTok;
-    tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane);
-    tile_load_async<kRot4>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane);
+    uint32_t kdoff[4], vdoff[4];
+    tile_lane_offsets<kXor16>(kdoff, wave, lane);
+    tile_lane_offsets<kRot4>(vdoff, wave, lane);
+    tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane, kdoff);
+    tile_load_async<kRot4>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane, vdoff);
     for (int it = 0; it < n_tiles; ++it) {
         wait_async_loads();
         __syncthreads();            // tile `it` is in LDS; everyone is done with the other slots
         if (it + 1 < n_tiles) {
-            tile_load_async<kXor16>(kh, t_begin + (it + 1) * kTileTok, len - 1, lds0 + (((it + 1) & 1) ? kLdsK1 : kLdsK0), wave, lane);
-            tile_load_async<kRot4>(vh, t_begin + (it + 1) * kTileTok, len - 1, lds0 + (((it + 1) & 1) ? kLdsV1 : kLdsV0), wave, lane);
+            tile_load_async<kXor16>(kh, t_begin + (it + 1) * kTileTok, len - 1, lds0 + (((it + 1) & 1) ? kLdsK1 : kLdsK0), wave, lane, kdoff);
+            tile_load_async<kRot4>(vh, t_begin + (it + 1) * kTileTok, len - 1, lds0 + (((it + 1) & 1) ? kLdsV1 : kLdsV0), wave, lane, vdoff);
         }
         if (!wave_active) continue;
         const char *ktile = smem + ((it & 1) ? kLdsK1 : kLdsK0);
@@ -767,8 +794,8 @@ template <int PH, bool kMasked, int kVariant>
 __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uint32_t lds0, int n, int n_blk,
                                             int t_begin, int t_end, int last_row, const int *vis_i,
                                             const int *excl_i, const char *kh, const char *vh,
-                                            const int (&koff)[8], int wave, int lane, bool wave_active,
-                                            float *plane_w) {
+                                            const int (&koff)[8], const uint32_t (&kdoff)[4], int wave, int lane,
+                                            bool wave_active, float *plane_w) {
     constexpr int kNv = kVariant == OBC_ALL ? 3 : 1;
     constexpr bool kDoV = kVariant == OBC_VALUE || kVariant == OBC_ALL;
     constexpr bool kDoK = kVariant == OBC_KEY || kVariant == OBC_ALL;
@@ -785,8 +812,8 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
         __syncthreads();
         const int tn = t_begin + ((n >> 1) + 1) * kTileTok;           // first token of the tile to start now
         if (tn < t_end) {
-            tile_load_async<kXor16>(kh, tn, last_row, lds0 + (PH == 0 ? kLdsK1 : kLdsK0), wave, lane);
-            tile_load_async<kXor16>(vh, tn, last_row, lds0 + (PH == 0 ? kLdsV1 : kLdsV0), wave, lane);
+            tile_load_async<kXor16>(kh, tn, last_row, lds0 + (PH == 0 ? kLdsK1 : kLdsK0), wave, lane, kdoff);
+            tile_load_async<kXor16>(vh, tn, last_row, lds0 + (PH == 0 ? kLdsV1 : kLdsV0), wave, lane, kdoff);
         }
     }
     if (n >= n_blk) return;                                            // uniform
@@ -946,14 +973,16 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
     const bool has_special = __syncthreads_or(mine_special) != 0;
 
     // Tile 0 is started here; step 0 waits for it.
-    tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane);
-    tile_load_async<kXor16>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane);
+    uint32_t kdoff[4];
+    tile_lane_offsets<kXor16>(kdoff, wave, lane);
+    tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane, kdoff);
+    tile_load_async<kXor16>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane, kdoff);
 
     const int n_blk = (t_end - t_begin + 31) / 32;
     const int n_total = (n_blk + 3) & ~3;
     int n_plain = (vis_min + 1 - t_begin) / 32;
     n_plain = has_special ? 0 : (max(0, min(n_plain, n_blk)) & ~3);
-#define OBC_S2_ARGS smem, lds0, n, n_blk, t_begin, t_end, len - 1, vis_i, excl_i, kh, vh, koff, wave, lane, wave_active, plane_w
+#define OBC_S2_ARGS smem, lds0, n, n_blk, t_begin, t_end, len - 1, vis_i, excl_i, kh, vh, koff, kdoff, wave, lane, wave_active, plane_w
     int n = 0;
     for (; n < n_plain; n += 4) {
         sweep2_step<0, false, kVariant>(R, OBC_S2_ARGS); ++n;

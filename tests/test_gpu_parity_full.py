@@ -1,0 +1,98 @@
+"""GPU parity at the benchmark's full sizes (configs c3, c4, c5), in the launch configuration
+bench.py times.  The fp64 oracle scores a sample of KV heads in full; every head is checked
+through properties that hold at any size (finite, non-negative, zero padding, selection
+bit-exact against the oracle's select on the same fp32 scores, byte-exact compaction)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2510_07651_amd import binding as obc
+from paper_2510_07651_amd import synth
+
+from parity_util import (TOL, check_keep_idx_valid, check_selection_against_oracle_scores, oracle_scores,
+                         score_error, to_device)
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_heads(wl, x, gpu_scores, heads, variant_idx):
+    """gpu_scores: [B,Hkv,N] numpy of one variant; oracle on the sampled (b, g) heads."""
+    tol = TOL[wl.dtype]
+    refs = oracle_scores(x, heads)
+    worst = 0.0
+    for (b, g), ref3 in zip(heads, refs):
+        lens = None if x["seq_lens"] is None else [x["seq_lens"][b]]
+        err, where = score_error(gpu_scores[b:b + 1, g:g + 1], ref3[variant_idx], wl.budget, lens, tol)
+        assert err <= tol, "%s head (%d,%d): err %.3g at %s" % (wl.name, b, g, err, where)
+        worst = max(worst, err)
+    return worst, refs
+
+
+def _pipeline_checks(wl, x, dev, scores_t):
+    lens = x["seq_lens"]
+    s_np = scores_t.cpu().numpy()
+    assert np.isfinite(s_np).all() and (s_np >= 0).all()
+    if lens is not None:
+        for b, L in enumerate(lens):
+            assert (s_np[b, :, L:] == 0).all()
+    keep = obc.obc_select(scores_t, wl.budget, seq_lens=lens)
+    keep_np = keep.cpu().numpy()
+    check_keep_idx_valid(keep_np, wl.budget, lens, wl.N)
+    np.testing.assert_array_equal(keep_np, oracle.select(s_np, wl.budget, lens))
+    k_out, v_out = obc.obc_compact(dev["k"], dev["v"], keep)
+    idx = keep.long().unsqueeze(-1).expand(-1, -1, -1, wl.d)
+    assert torch.equal(k_out, torch.gather(dev["k"], 2, idx))
+    assert torch.equal(v_out, torch.gather(dev["v"], 2, idx))
+    return keep_np
+
+
+def test_c3_llama_b4_32k_joint():
+    wl = synth.config("c3")
+    x = synth.make_inputs(wl)
+    dev = to_device(x)
+    s = obc.obc_score(dev["q"], dev["k"], dev["v"], "joint")
+    torch.cuda.synchronize()
+    heads = [(0, 0), (2, 5), (3, 7)]
+    worst, refs = _check_heads(wl, x, s.cpu().numpy(), heads, 2)
+    keep_np = _pipeline_checks(wl, x, dev, s)
+    for (b, g), ref3 in zip(heads, refs):
+        check_selection_against_oracle_scores(keep_np[b:b + 1, g:g + 1], ref3[2], wl.budget, None, TOL[wl.dtype])
+    print("c3 worst sampled error %.2e" % worst)
+
+
+def test_c4_qwen_128k_all_variants():
+    wl = synth.config("c4")
+    x = synth.make_inputs(wl)
+    dev = to_device(x)
+    s = obc.obc_score(dev["q"], dev["k"], dev["v"], "all")
+    torch.cuda.synchronize()
+    heads = [(0, 2)]
+    refs = oracle_scores(x, heads)
+    for vi, name in enumerate(synth.VARIANTS):
+        g_np = s[vi].cpu().numpy()
+        for (b, g), ref3 in zip(heads, refs):
+            err, where = score_error(g_np[b:b + 1, g:g + 1], ref3[vi], wl.budget, None, TOL[wl.dtype])
+            assert err <= TOL[wl.dtype], "c4 %s: err %.3g at %s" % (name, err, where)
+            print("c4", name, "sampled head error %.2e" % err)
+        keep_np = _pipeline_checks(wl, x, dev, s[vi].contiguous())
+        for (b, g), ref3 in zip(heads, refs):
+            check_selection_against_oracle_scores(keep_np[b:b + 1, g:g + 1], ref3[vi], wl.budget, None,
+                                                  TOL[wl.dtype])
+
+
+@pytest.mark.parametrize("layer", [0, 31])
+def test_c5_ragged_layers(layer):
+    wl = synth.config("c5")
+    x = synth.make_inputs(wl, layer=layer)
+    dev = to_device(x)
+    lens = x["seq_lens"]
+    s = obc.obc_score(dev["q"], dev["k"], dev["v"], "joint", seq_lens=lens)
+    torch.cuda.synchronize()
+    heads = [(0, 3), (1, 6)]
+    worst, refs = _check_heads(wl, x, s.cpu().numpy(), heads, 2)
+    keep_np = _pipeline_checks(wl, x, dev, s)
+    for (b, g), ref3 in zip(heads, refs):
+        check_selection_against_oracle_scores(keep_np[b:b + 1, g:g + 1], ref3[2], wl.budget, [lens[b]],
+                                              TOL[wl.dtype])
+    print("c5 layer", layer, "lens", lens, "worst sampled error %.2e" % worst)
