@@ -33,6 +33,8 @@
 // expression is the exact squared distance to o^_i.
 //
 // A and Z never touch HBM.  All sums have a fixed order: results are bit-reproducible.
+#include <cstdlib>
+
 #include "internal.h"
 
 namespace obc {
@@ -52,6 +54,14 @@ constexpr int kTileBytes = kTileTok * kRowBytes;   // 16 KB
 constexpr int kThreads = 256;           // 4 waves; wave w owns row block 4*chunk + w (32 window rows)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kInvSqrtD = 0.08838834764831845f;   // 1/sqrt(128)
+// The running softmax sums of sweep 1 are kept relative to a reference that follows the
+// running max lazily: it only moves (and the accumulated O is only rescaled) when the max
+// has grown by more than 8 in log2 units, so weights stay below 2^8 and the 64-register
+// rescale becomes rare instead of happening whenever any of a wave's 32 rows sees a new max.
+constexpr float kLazyRescale = 8.0f / (kLog2e * kInvSqrtD);   // in raw q.k units
+
+// Rows with A_top = 1 / row sum above this share of the attention are rescued (see below).
+constexpr float kDominantShare = 0.9f;
 
 // LDS map (bytes): two K tiles, then two V tiles.
 constexpr int kLdsK0 = 0, kLdsK1 = kTileBytes, kLdsV0 = 2 * kTileBytes, kLdsV1 = 3 * kTileBytes;
@@ -192,7 +202,8 @@ struct Sweep1Regs {
     f32x16 oacc[4];       // O^T accumulators: head_dim block x 16 registers
     f32x16 s_cur;         // raw q.k of the block whose softmax is due
     PiecePair phi[2], plo[2];   // two-piece softmax weights of the previous block, per k-step
-    float m_raw, lsum;    // running max of raw q.k; this lane's share of the running sum
+    float m_ref, m_true;  // reference of the running sums (raw q.k units, see kLazyRescale); true running max
+    float lsum;           // this lane's share of the running sum
     float alpha;          // rescale of oacc still owed from the previous step (1 = none)
     bool rescale;         // uniform: some row of the wave owes a rescale
 };
@@ -265,15 +276,16 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
     for (int r = 3; r < 15; r += 2) mx = max3(mx, s[r], s[r + 1]);
     mx = fmaxf(mx, s[15]);
     mx = fmaxf(mx, other_half(mx));
-    const float m_new = fmaxf(R.m_raw, mx);
-    const bool moved = m_new > R.m_raw;
-    float alpha = __builtin_amdgcn_exp2f((R.m_raw - m_new) * c2);     // exp2(-inf) = 0
+    R.m_true = fmaxf(R.m_true, mx);
+    const bool moved = mx > R.m_ref + kLazyRescale;                    // also true for the first visible key
+    const float m_new = moved ? mx : R.m_ref;
+    float alpha = __builtin_amdgcn_exp2f((R.m_ref - m_new) * c2);      // 1 when the reference stays; exp2(-inf) = 0
     float mref = m_new * c2;
     if (kMasked) {                                                     // rows with nothing visible yet
         alpha = moved ? alpha : 1.0f;
         mref = m_new == -INFINITY ? 0.f : mref;
     }
-    R.m_raw = m_new;
+    R.m_ref = m_new;
     float p[16], psum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
@@ -307,10 +319,12 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
                                                            const uint16_t *__restrict__ v, int N, int W, int Hq,
                                                            int Hkv, int ragged, SeqLens lens, int split_len,
                                                            int n_splits, int m_pad, float *__restrict__ part_ml,
-                                                           float *__restrict__ part_o) {
+                                                           float *__restrict__ part_o,
+                                                           int32_t *__restrict__ dom_count) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
 
     const int split = blockIdx.x, chunk = blockIdx.y, bg = blockIdx.z;
+    if (split == 0 && chunk == 0 && threadIdx.x == 0) dom_count[bg] = 0;   // filled by the combine step
     const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv, M = G * W;
     const int len = seq_len_of(lens, ragged, b, N);
     const int t_begin = split * split_len;
@@ -356,7 +370,8 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
     for (int sx = 0; sx < 2; ++sx)
 #pragma unroll
         for (int e = 0; e < 4; ++e) { R.phi[sx].u[e] = 0; R.plo[sx].u[e] = 0; }
-    R.m_raw = -INFINITY;
+    R.m_ref = -INFINITY;
+    R.m_true = -INFINITY;
     R.lsum = 0.f;
     R.alpha = 1.0f;
     R.rescale = false;
@@ -423,8 +438,9 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
     const float lrow = R.lsum + other_half(R.lsum);
     const size_t prow = ((size_t)bg * n_splits + split) * m_pad + row;
     if (half == 0) {
-        part_ml[prow * 4 + 0] = R.m_raw;         // raw q.k units; -inf when the split holds no visible key
+        part_ml[prow * 4 + 0] = R.m_ref;         // raw q.k units; -inf when the split holds no visible key
         part_ml[prow * 4 + 1] = lrow;
+        part_ml[prow * 4 + 2] = R.m_true;
     }
     if (kNeedO) {
         float *dst = part_o + prow * kD;
@@ -448,7 +464,8 @@ __global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ pa
                                                     int m_pad, int need_o, float *__restrict__ row_max,
                                                     float *__restrict__ row_sum, float *__restrict__ out_f32,
                                                     uint16_t *__restrict__ out_bf16, float *__restrict__ row_const,
-                                                    float *__restrict__ special) {
+                                                    float *__restrict__ special, int32_t *__restrict__ dom_rows,
+                                                    int32_t *__restrict__ dom_count) {
     __shared__ float red[2];
     const int row = blockIdx.x, bg = blockIdx.y;
     const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv, M = G * W;
@@ -471,11 +488,12 @@ __global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ pa
     const int live_splits = (len + split_len - 1) / split_len;
     const float c2 = kLog2e * kInvSqrtD;
     float m_raw = -INFINITY;                          // max over the row of the raw dot product q.k
-    for (int s = 0; s < live_splits; ++s) m_raw = fmaxf(m_raw, part_ml[(((size_t)bg * n_splits + s) * m_pad + row) * 4]);
+    for (int s = 0; s < live_splits; ++s) m_raw = fmaxf(m_raw, part_ml[(((size_t)bg * n_splits + s) * m_pad + row) * 4 + 2]);
     float l = 0.f, o = 0.f;
+#pragma unroll 8
     for (int s = 0; s < live_splits; ++s) {
         const size_t prow = ((size_t)bg * n_splits + s) * m_pad + row;
-        const float w = exp2f((part_ml[prow * 4] - m_raw) * c2);  // 0 for splits hidden from this row
+        const float w = exp2f((part_ml[prow * 4] - m_raw) * c2);  // partial sums are relative to their own reference
         l = fmaf(w, part_ml[prow * 4 + 1], l);
         if (need_o) o = fmaf(w, part_o[prow * kD + dd], o);
     }
@@ -503,6 +521,9 @@ __global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ pa
         row_const[crow * 4 + 2] = __int_as_float(len - W + (row % W));
         row_const[crow * 4 + 3] = m_raw;
         special[crow * 4 + 0] = __int_as_float(-1);        // no separately scored (row, token) pair yet
+        // Rows whose top key dominates join the KV head's rescue list (any order: each row is
+        // rescued on its own; the count was cleared by sweep 1).
+        if (need_o && l * kDominantShare < 1.0f) dom_rows[crow - row + atomicAdd(&dom_count[bg], 1)] = row;
     }
 }
 
@@ -513,34 +534,12 @@ __global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ pa
 // top is then unique) has o_i ~ v_top, and fp32 sums that contain the top key's weight 1
 // cannot resolve v_top - o_i: the expanded norm loses its last digits near A_top ~ 0.99,
 // so rows are taken out well before that.  Such rows are rare (retrieval-like heads).  They are
-// gathered per KV head and swept once more with the row max known: the top key is left
+// listed per KV head by the combine step and swept once more with the row max known: the top key is left
 // out of the sums, which gives l' = sum_{q != top} exp(z_q - z_top) and O' = sum_{q != top}
 // exp(z_q - z_top) v_q, and then exactly
 //     v_top - o_i = l' / (1 + l') * (v_top - O' / l'),      o_i = v_top - (v_top - o_i).
 // The (row, top key) pair is scored from these in fp32 (`special`), the second sweep skips
 // that pair and adds the stored values, and uses the refreshed o_i for all other keys.
-constexpr float kDominantShare = 0.9f;
-
-// One block per KV head: the dominant rows in row order, then their count.
-__global__ __launch_bounds__(512) void mfma_dominant_list(const float *__restrict__ row_sum, int W, int Hq, int Hkv,
-                                                          int m_pad, int32_t *__restrict__ dom_rows,
-                                                          int32_t *__restrict__ dom_count) {
-    __shared__ int wave_tot[8];
-    const int bg = blockIdx.x, b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv, M = G * W;
-    const int row = threadIdx.x, lane = row & 63, wave = row >> 6;
-    const size_t grow = ((size_t)b * Hq + (size_t)g * G) * W + row;
-    const bool dom = row < M && row_sum[row < M ? grow : 0] * kDominantShare < 1.0f;
-    const unsigned long long bal = __ballot(dom);
-    if (lane == 0) wave_tot[wave] = __popcll(bal);
-    __syncthreads();
-    int before = __popcll(bal & ((1ull << lane) - 1ull)), total = 0;
-    for (int w = 0; w < 8; ++w) {
-        if (w < wave) before += wave_tot[w];
-        total += wave_tot[w];
-    }
-    if (dom) dom_rows[(size_t)bg * m_pad + before] = row;
-    if (row == 0) dom_count[bg] = total;
-}
 
 // Grid: x = sequence split, y = 128-row chunk of the dominant list, z = (b, KV head).
 __global__ __launch_bounds__(kThreads, 2) void mfma_rescue_sweep(const uint16_t *__restrict__ q,
@@ -749,11 +748,7 @@ hipError_t launch_rescue(const ScoreArgs &a, const ScoreWorkspace &ws, char *bas
     int32_t *dom_rows = (int32_t *)(base + ws.dom_rows);
     int32_t *dom_count = dom_rows + (size_t)BH * ws.m_pad;
     float *part_ml = (float *)(base + ws.part_ml), *part_o = (float *)(base + ws.part_o);
-    mfma_dominant_list<<<dim3(BH), dim3(512), 0, stream>>>((const float *)(base + ws.row_sum), a.W, a.Hq, a.Hkv,
-                                                           ws.m_pad, dom_rows, dom_count);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)mfma_rescue_sweep, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTiles);
+    hipError_t e = hipFuncSetAttribute((const void *)mfma_rescue_sweep, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTiles);
     if (e != hipSuccess) return e;
     mfma_rescue_sweep<<<dim3(ws.splits, ws.n_chunks, BH), dim3(kThreads), kLdsTiles, stream>>>(
         (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens,
@@ -794,7 +789,7 @@ template <int PH, bool kMasked, int kVariant>
 __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uint32_t lds0, int n, int n_blk,
                                             int t_begin, int t_end, int last_row, const int *vis_i,
                                             const int *excl_i, const char *kh, const char *vh,
-                                            const int (&koff)[8], const uint32_t (&kdoff)[4], int wave, int lane,
+                                            const char *const (&kp)[8], const uint32_t (&kdoff)[4], int wave, int lane,
                                             bool wave_active, float *plane_w) {
     constexpr int kNv = kVariant == OBC_ALL ? 3 : 1;
     constexpr bool kDoV = kVariant == OBC_VALUE || kVariant == OBC_ALL;
@@ -824,12 +819,12 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
         float vv = 0.f;
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
-            const bf16x8 kb = lds_read16(smem + kKBase + koff[kk]);
+            const bf16x8 kb = lds_read16(kp[kk] + kKBase);
             z = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.q[kk], kb, z, 0, 0, 0);
         }
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
-            const bf16x8 vb = lds_read16(smem + kVBase + koff[kk]);
+            const bf16x8 vb = lds_read16(kp[kk] + kVBase);
             vv = sumsq8(vb, vv);
             if (kNeedVO) {
                 vo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.ohi[kk], vb, vo, 0, 0, 0);
@@ -924,6 +919,10 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) koff[kk] = row_piece_offset(lane, kk);
 
+    const char *kp[8];                                         // LDS address of this lane's operand piece kk in a tile at offset 0
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) kp[kk] = smem + koff[kk];
+
     Sweep2Regs R;
     {
         const bool ok = arow < M;
@@ -982,7 +981,7 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
     const int n_total = (n_blk + 3) & ~3;
     int n_plain = (vis_min + 1 - t_begin) / 32;
     n_plain = has_special ? 0 : (max(0, min(n_plain, n_blk)) & ~3);
-#define OBC_S2_ARGS smem, lds0, n, n_blk, t_begin, t_end, len - 1, vis_i, excl_i, kh, vh, koff, kdoff, wave, lane, wave_active, plane_w
+#define OBC_S2_ARGS smem, lds0, n, n_blk, t_begin, t_end, len - 1, vis_i, excl_i, kh, vh, kp, kdoff, wave, lane, wave_active, plane_w
     int n = 0;
     for (; n < n_plain; n += 4) {
         sweep2_step<0, false, kVariant>(R, OBC_S2_ARGS); ++n;
@@ -1066,9 +1065,17 @@ void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWo
     int splits = (512 + BH * ws->n_chunks - 1) / (BH * ws->n_chunks);
     const int max_splits = (N + 511) / 512;
     splits = splits < 1 ? 1 : (splits > max_splits ? max_splits : splits);
+    if (const char *e = std::getenv("OBC_TUNE_SPLITS")) {          // tuning knobs for experiments
+        const int v = std::atoi(e);
+        if (v >= 1 && v <= max_splits) splits = v;
+    }
     ws->split_len = ((N + splits - 1) / splits + kTileTok - 1) / kTileTok * kTileTok;
     ws->splits = (N + ws->split_len - 1) / ws->split_len;
     ws->range_len = 512;
+    if (const char *e = std::getenv("OBC_TUNE_RANGE")) {
+        const int v = std::atoi(e);
+        if (v >= 64 && v <= 768 && v % 64 == 0) ws->range_len = v;
+    }
     const size_t rows = (size_t)BH * ws->m_pad;
     ws->out_bf16 = *off;  *off = align_up(*off + 2 * rows * d * 2, 256);   // high pieces, then residual pieces
     ws->row_const = *off; *off = align_up(*off + rows * 4 * sizeof(float), 256);
@@ -1083,6 +1090,8 @@ void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWo
 hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStream_t stream) {
     const bool need_o = a.variant != OBC_VALUE;
     float *part_ml = (float *)(base + ws.part_ml), *part_o = (float *)(base + ws.part_o);
+    int32_t *dom_rows = (int32_t *)(base + ws.dom_rows);
+    int32_t *dom_count = dom_rows + (size_t)a.B * a.Hkv * ws.m_pad;
     hipError_t e = hipSuccess;
     if (a.stage_mask & OBC_STAGE_SWEEP1) {
         const size_t lds = kLdsTiles;
@@ -1093,11 +1102,11 @@ hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char 
         if (need_o)
             mfma_sweep1<true><<<grid, dim3(kThreads), lds, stream>>>(
                 (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged,
-                a.lens, ws.split_len, ws.splits, ws.m_pad, part_ml, part_o);
+                a.lens, ws.split_len, ws.splits, ws.m_pad, part_ml, part_o, dom_count);
         else
             mfma_sweep1<false><<<grid, dim3(kThreads), lds, stream>>>(
                 (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged,
-                a.lens, ws.split_len, ws.splits, ws.m_pad, part_ml, part_o);
+                a.lens, ws.split_len, ws.splits, ws.m_pad, part_ml, part_o, dom_count);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -1106,7 +1115,7 @@ hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char 
             part_ml, part_o, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, ws.split_len, ws.splits, ws.m_pad,
             need_o ? 1 : 0, (float *)(base + ws.row_max), (float *)(base + ws.row_sum),
             (float *)(base + ws.out_f32), (uint16_t *)(base + ws.out_bf16), (float *)(base + ws.row_const),
-            (float *)(base + ws.special));
+            (float *)(base + ws.special), dom_rows, dom_count);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         if (need_o) {
