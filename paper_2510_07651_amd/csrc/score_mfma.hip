@@ -487,15 +487,35 @@ __global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ pa
     }
     const int live_splits = (len + split_len - 1) / split_len;
     const float c2 = kLog2e * kInvSqrtD;
-    float m_raw = -INFINITY;                          // max over the row of the raw dot product q.k
-    for (int s = 0; s < live_splits; ++s) m_raw = fmaxf(m_raw, part_ml[(((size_t)bg * n_splits + s) * m_pad + row) * 4 + 2]);
-    float l = 0.f, o = 0.f;
-#pragma unroll 8
-    for (int s = 0; s < live_splits; ++s) {
-        const size_t prow = ((size_t)bg * n_splits + s) * m_pad + row;
-        const float w = exp2f((part_ml[prow * 4] - m_raw) * c2);  // partial sums are relative to their own reference
-        l = fmaf(w, part_ml[prow * 4 + 1], l);
-        if (need_o) o = fmaf(w, part_o[prow * kD + dd], o);
+    // Splits are merged sixteen at a time, every load of a batch issued before the first use,
+    // so that a row costs one memory round trip per batch.  The running sums follow the
+    // running max of the raw dot products; a split's sums are relative to its own reference.
+    float m_raw = -INFINITY, l = 0.f, o = 0.f;
+    for (int s0 = 0; s0 < live_splits; s0 += 16) {
+        float4 ml[16];
+        float po[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int s = min(s0 + j, live_splits - 1);       // clamped slots are ignored below
+            const size_t prow = ((size_t)bg * n_splits + s) * m_pad + row;
+            ml[j] = ((const float4 *)part_ml)[prow];
+            po[j] = need_o ? part_o[prow * kD + dd] : 0.f;
+        }
+        float m_new = m_raw;
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if (s0 + j < live_splits) m_new = fmaxf(m_new, ml[j].z);
+        const float keep = m_raw == -INFINITY ? 0.f : exp2f((m_raw - m_new) * c2);
+        l *= keep;
+        o *= keep;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            if (s0 + j >= live_splits) continue;
+            const float w = ml[j].x == -INFINITY ? 0.f : exp2f((ml[j].x - m_new) * c2);
+            l = fmaf(w, ml[j].y, l);
+            o = fmaf(w, po[j], o);
+        }
+        m_raw = m_new;
     }
     const float m = m_raw * c2;                       // log2 units
     o = o / l;
@@ -779,6 +799,17 @@ struct Sweep2Regs {
     float c_m2[16], c_oo[16];      // per accumulator register: 2 (max + log2 sum), ||o^||^2 of its row
 };
 
+// Adds up, in wave order, the four waves' partial scores of one tile (64 tokens starting at
+// `tok0`, staged in LDS as [wave][variant][64]) and writes them out; wave c handles variant c.
+template <int kNv>
+__device__ __forceinline__ void sweep2_flush(const float *stage, float *out, size_t variant_stride, int tok0,
+                                             int t_end, int wave, int lane) {
+    if (wave < kNv && tok0 + lane < t_end) {
+        const float *p = stage + wave * 64 + lane;
+        out[wave * variant_stride + tok0 + lane] = (p[0] + p[kNv * 64]) + (p[2 * kNv * 64] + p[3 * kNv * 64]);
+    }
+}
+
 // One step of sweep 2 = one block of 32 tokens (PH = n mod 4 fixes the LDS slot):
 //   matrix cores: Z = Q K^T and O V^T of the block (+ ||v||^2 on the dot-product unit)
 //   vector ALUs : its scores, summed over this wave's 32 rows, parked in LDS
@@ -790,7 +821,7 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
                                             int t_begin, int t_end, int last_row, const int *vis_i,
                                             const int *excl_i, const char *kh, const char *vh,
                                             const char *const (&kp)[8], const uint32_t (&kdoff)[4], int wave, int lane,
-                                            bool wave_active, float *plane_w) {
+                                            bool wave_active, float *part, float *out, size_t variant_stride) {
     constexpr int kNv = kVariant == OBC_ALL ? 3 : 1;
     constexpr bool kDoV = kVariant == OBC_VALUE || kVariant == OBC_ALL;
     constexpr bool kDoK = kVariant == OBC_KEY || kVariant == OBC_ALL;
@@ -810,6 +841,7 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
             tile_load_async<kXor16>(kh, tn, last_row, lds0 + (PH == 0 ? kLdsK1 : kLdsK0), wave, lane, kdoff);
             tile_load_async<kXor16>(vh, tn, last_row, lds0 + (PH == 0 ? kLdsV1 : kLdsV0), wave, lane, kdoff);
         }
+        if (n >= 2) sweep2_flush<kNv>(part + (kSlot ^ 1) * 4 * kNv * 64, out, variant_stride, t_begin + (n - 2) * 32, t_end, wave, lane);
     }
     if (n >= n_blk) return;                                            // uniform
     float acc_v = 0.f, acc_k = 0.f, acc_j = 0.f;
@@ -861,11 +893,11 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
         if (kDoJ) acc_j += other_half(acc_j);
     }
     if (half == 0) {
-        float *pw = plane_w + (n * 32 + lane) * kNv;
+        float *pw = part + ((kSlot * 4 + wave) * kNv) * 64 + kBlk * 32 + lane;
         int c = 0;
-        if (kDoV) pw[c++] = acc_v;
-        if (kDoK) pw[c++] = acc_k;
-        if (kDoJ) pw[c++] = acc_j;
+        if (kDoV) pw[64 * c++] = acc_v;
+        if (kDoK) pw[64 * c++] = acc_k;
+        if (kDoJ) pw[64 * c++] = acc_j;
     }
 }
 
@@ -887,7 +919,7 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     float *vis_s = (float *)(smem + kLdsTiles);                // [128] last visible key of each row of the chunk
     float *excl_s = vis_s + 128;                               // [128] key of the row that is scored separately, or -1
-    float *plane = excl_s + 128;                               // [4 waves][range_len][kNv]
+    float *part = excl_s + 128;                                // [2 tiles][4 waves][kNv][64] partial scores
 
     const int range = blockIdx.x, chunk = blockIdx.y, bg = blockIdx.z;
     const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv, M = G * W;
@@ -914,6 +946,13 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
     const char *kh = (const char *)k + (size_t)bg * N * kRowBytes;
     const char *vh = (const char *)v + (size_t)bg * N * kRowBytes;
     const uint32_t lds0 = lds_offset_of(smem);
+
+    // Tile 0 is started before anything else so that its latency hides behind the loads of
+    // this wave's stationary operands; step 0 waits for it.
+    uint32_t kdoff[4];
+    tile_lane_offsets<kXor16>(kdoff, wave, lane);
+    tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane, kdoff);
+    tile_load_async<kXor16>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane, kdoff);
 
     int koff[8];
 #pragma unroll
@@ -944,9 +983,10 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
     for (int r = 0; r < 16; ++r) {
         const int i = rb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
         const bool ok = wave_active && i < m_pad;
-        R.c_m2[r] = ok ? row_const[(cbase + i) * 4 + 0] : 1e30f;      // padded rows weigh nothing
-        R.c_oo[r] = ok ? row_const[(cbase + i) * 4 + 1] : 0.f;
-        const int vi = ok ? __float_as_int(row_const[(cbase + i) * 4 + 2]) : -1;
+        const float4 rc = ok ? ((const float4 *)row_const)[cbase + i] : make_float4(1e30f, 0.f, __int_as_float(-1), 0.f);
+        R.c_m2[r] = rc.x;                                              // padded rows (1e30) weigh nothing
+        R.c_oo[r] = rc.y;
+        const int vi = __float_as_int(rc.z);
         if (vi >= 0) vis_min = min(vis_min, vi);
     }
     vis_min = min(vis_min, __shfl_xor(vis_min, 32));
@@ -967,21 +1007,14 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
         mine_special = ex >= t_begin && ex < t_end;
     }
     const int *vis_i = (const int *)vis_s, *excl_i = (const int *)excl_s;
-    float *plane_w = plane + (size_t)wave * range_len * kNv;
     // Uniform: some (row, key) pair of this chunk and token range is scored separately.
     const bool has_special = __syncthreads_or(mine_special) != 0;
-
-    // Tile 0 is started here; step 0 waits for it.
-    uint32_t kdoff[4];
-    tile_lane_offsets<kXor16>(kdoff, wave, lane);
-    tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane, kdoff);
-    tile_load_async<kXor16>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane, kdoff);
 
     const int n_blk = (t_end - t_begin + 31) / 32;
     const int n_total = (n_blk + 3) & ~3;
     int n_plain = (vis_min + 1 - t_begin) / 32;
     n_plain = has_special ? 0 : (max(0, min(n_plain, n_blk)) & ~3);
-#define OBC_S2_ARGS smem, lds0, n, n_blk, t_begin, t_end, len - 1, vis_i, excl_i, kh, vh, kp, kdoff, wave, lane, wave_active, plane_w
+#define OBC_S2_ARGS smem, lds0, n, n_blk, t_begin, t_end, len - 1, vis_i, excl_i, kh, vh, kp, kdoff, wave, lane, wave_active, part, out, variant_stride
     int n = 0;
     for (; n < n_plain; n += 4) {
         sweep2_step<0, false, kVariant>(R, OBC_S2_ARGS); ++n;
@@ -997,17 +1030,11 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
     }
 #undef OBC_S2_ARGS
     __syncthreads();
-    for (int t = threadIdx.x; t < t_stop - t_begin; t += kThreads) {
-        const bool live = t_begin + t < t_end;
+    // The last tile's partial sums (second staging slot: n_total is a multiple of 4), then zeros for the padding.
+    sweep2_flush<kNv>(part + 4 * kNv * 64, out, variant_stride, t_begin + (n_total - 2) * 32, t_end, wave, lane);
+    for (int t = t_end + threadIdx.x; t < t_stop; t += kThreads)
 #pragma unroll
-        for (int c = 0; c < kNv; ++c) {
-            float s = 0.f;
-            if (live)
-                s = (plane[((size_t)0 * range_len + t) * kNv + c] + plane[((size_t)1 * range_len + t) * kNv + c]) +
-                    (plane[((size_t)2 * range_len + t) * kNv + c] + plane[((size_t)3 * range_len + t) * kNv + c]);
-            out[c * variant_stride + t_begin + t] = s;
-        }
-    }
+        for (int c = 0; c < kNv; ++c) out[c * variant_stride + t] = 0.f;
     if (has_special) {      // add the separately scored pairs, in row order, by one thread
         __syncthreads();
         if (threadIdx.x == 0) {
@@ -1037,7 +1064,7 @@ __global__ __launch_bounds__(256) void mfma_sum_planes(const float *__restrict__
 template <int kVariant>
 hipError_t launch_sweep2(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStream_t stream) {
     constexpr int nv = kVariant == OBC_ALL ? 3 : 1;
-    const size_t lds = kLdsTiles + 256 * sizeof(float) + (size_t)4 * ws.range_len * nv * sizeof(float);
+    const size_t lds = kLdsTiles + 256 * sizeof(float) + (size_t)2 * 4 * nv * 64 * sizeof(float);
     hipError_t e = hipFuncSetAttribute((const void *)mfma_sweep2<kVariant>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     const size_t plane_elems = (size_t)a.B * a.Hkv * a.N;
@@ -1071,10 +1098,15 @@ void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWo
     }
     ws->split_len = ((N + splits - 1) / splits + kTileTok - 1) / kTileTok * kTileTok;
     ws->splits = (N + ws->split_len - 1) / ws->split_len;
-    ws->range_len = 512;
+    // Token range of one sweep-2 block: about two blocks per compute unit over the whole launch.
+    {
+        const long long units = (long long)N * BH * ws->n_chunks;
+        long long r = ((units + 511) / 512 + 63) / 64 * 64;
+        ws->range_len = (int)(r < 128 ? 128 : (r > 8192 ? 8192 : r));
+    }
     if (const char *e = std::getenv("OBC_TUNE_RANGE")) {
         const int v = std::atoi(e);
-        if (v >= 64 && v <= 768 && v % 64 == 0) ws->range_len = v;
+        if (v >= 64 && v <= 65536 && v % 64 == 0) ws->range_len = v;
     }
     const size_t rows = (size_t)BH * ws->m_pad;
     ws->out_bf16 = *off;  *off = align_up(*off + 2 * rows * d * 2, 256);   // high pieces, then residual pieces
