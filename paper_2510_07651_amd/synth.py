@@ -145,4 +145,13 @@ def small_cases() -> List[Workload]:
         Workload("s_bf16_strong_sink", B=1, Hq=8, Hkv=2, d=128, N=1200, W=32, dtype="bf16", budget=150, seed=17,
                  sinks=4, shared_query=1.0),
         Workload("s_bf16_tiny", B=1, Hq=4, Hkv=1, d=128, N=40, W=32, dtype="bf16", budget=33, seed=18, sinks=1),
+        # degenerate shapes: one query head per KV head with fewer window rows than a wave owns; a cache that
+        # is nothing but the window; many short ragged sequences; head_dim 64 in bf16; budget == length
+        Workload("s_bf16_mha_rows16", B=1, Hq=3, Hkv=3, d=128, N=777, W=16, dtype="bf16", budget=77, seed=19,
+                 sinks=1, outlier_channels=2),
+        Workload("s_bf16_window_only", B=2, Hq=8, Hkv=2, d=128, N=32, W=32, dtype="bf16", budget=32, seed=20),
+        Workload("s_bf16_many_short", B=37, Hq=4, Hkv=2, d=128, N=300, W=8, dtype="bf16", budget=8, seed=21,
+                 sinks=1, ragged=(8, 300), pad_nan=True),
+        Workload("s_bf16_d64", B=2, Hq=4, Hkv=2, d=64, N=500, W=16, dtype="bf16", budget=50, seed=22, sinks=2),
+        Workload("s_fp32_d128_w64", B=1, Hq=2, Hkv=1, d=128, N=260, W=64, dtype="fp32", budget=65, seed=23, sinks=1),
     ]
