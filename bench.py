@@ -121,10 +121,21 @@ def main():
         "obc_select": timed(select, it, torch),
         "obc_compact": timed(compact, it, torch),
     }
+    # The box's own streaming-read rate over the same K and V buffers (plain 128-bit loads).
+    sink = torch.empty(obc.OBC_PROBE_BLOCKS * 256, dtype=torch.int32, device=dev)
+
+    def stream(i):
+        s = sets[i & 1]
+        obc.obc_probe_read_bandwidth(s["k"], sink)
+        obc.obc_probe_read_bandwidth(s["v"], sink)
+
+    stream(0)
+    ms_stream = timed(stream, it, torch)
     esize = 2 if wl.dtype == "bf16" else 4
     head_tokens = tokens * Hkv
     algo_bytes = head_tokens * 2 * d * esize + B * Hq * W * d * esize + nvar * B * Hkv * N * 4
     achieved = algo_bytes / (ms["obc_score"] * 1e-3) / 1e9
+    mfma_flops = 4 * 2 * Hq * W * d * tokens
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % wl.name)
     if os.path.exists(tpath):
@@ -136,6 +147,11 @@ def main():
         "frac": round(achieved / PEAK_HBM_GBPS, 4), "traffic": traffic,
         "algorithmic_bytes": algo_bytes,
         "kernel_ms": {k: round(v, 4) for k, v in ms.items()},
+        # plain streaming read of the same K and V buffers on this machine: the practical ceiling
+        "stream_read_GBps": round(2 * sets[0]["k"].numel() * esize / (ms_stream * 1e-3) / 1e9, 1),
+        # the four dense contractions of the path (Q K^T twice, P V, O V^T) against the dense bf16 matrix-core peak
+        "mfma": {"flops": mfma_flops, "achieved_TFLOPs": round(mfma_flops / (ms["obc_score"] * 1e-3) / 1e12, 1),
+                 "peak_TFLOPs": 2500.0, "frac": round(mfma_flops / (ms["obc_score"] * 1e-3) / 2.5e15, 4)},
     }
 
     cpu = None

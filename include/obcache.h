@@ -137,6 +137,16 @@ int obc_compact(const void *k, const void *v, const int32_t *keep_idx,
                 void *k_out, void *v_out,
                 int B, int Hkv, int N, int budget, int d, int dtype, void *hip_stream);
 
+/*
+ * Measurement hook (not part of the method): reads `bytes` bytes (a multiple of 16, 16-byte
+ * aligned, device) once with 128-bit loads and writes one folded word per thread to
+ * `sink` (device, OBC_PROBE_BLOCKS * 256 uint32).  Timed with events around the call it
+ * gives the streaming-read rate this GPU actually sustains, which the benchmark prints
+ * next to the nominal HBM peak.
+ */
+#define OBC_PROBE_BLOCKS 2048
+int obc_probe_read_bandwidth(const void *buf, size_t bytes, uint32_t *sink, void *hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char *obc_status_string(int status);
 

@@ -56,6 +56,8 @@ def load_library():
     lib.obc_compact.restype = c_int
     lib.obc_compact.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int,
                                 c_int, c_void_p]
+    lib.obc_probe_read_bandwidth.restype = c_int
+    lib.obc_probe_read_bandwidth.argtypes = [c_void_p, c_size_t, c_void_p, c_void_p]
     _lib = lib
     return lib
 
@@ -168,3 +170,17 @@ def obc_compact(k: torch.Tensor, v: torch.Tensor, keep_idx: torch.Tensor, k_out=
     if rc != OBC_OK:
         raise ObcError(rc, "obc_compact")
     return k_out, v_out
+
+
+OBC_PROBE_BLOCKS = 2048
+
+
+def obc_probe_read_bandwidth(buf: torch.Tensor, sink: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Measurement hook: one streaming read of `buf` (time it with events around the call)."""
+    if sink is None:
+        sink = torch.empty(OBC_PROBE_BLOCKS * 256, dtype=torch.int32, device=buf.device)
+    nbytes = buf.numel() * buf.element_size()
+    rc = load_library().obc_probe_read_bandwidth(buf.data_ptr(), nbytes, sink.data_ptr(), _stream_ptr(buf))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_probe_read_bandwidth")
+    return sink

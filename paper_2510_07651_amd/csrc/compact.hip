@@ -22,7 +22,26 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4 *__restrict__ k, 
     out[t] = in[src];
 }
 
+// Measurement hook: reads `n_vec` 16-byte words once with 128-bit loads and folds them
+// into one word per thread (so the loads cannot be dropped).  Its duration gives the box's
+// own streaming-read ceiling, the practical denominator next to the nominal HBM peak.
+__global__ __launch_bounds__(256) void stream_read(const uint4 *__restrict__ src, size_t n_vec,
+                                                   uint32_t *__restrict__ sink) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += stride) {
+        const uint4 x = src[i];
+        acc.x ^= x.x; acc.y ^= x.y; acc.z ^= x.z; acc.w ^= x.w;
+    }
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = acc.x ^ acc.y ^ acc.z ^ acc.w;
+}
+
 }  // namespace
+
+hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int blocks, hipStream_t stream) {
+    stream_read<<<dim3(blocks), dim3(256), 0, stream>>>((const uint4 *)src, bytes / 16, sink);
+    return hipGetLastError();
+}
 
 hipError_t launch_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_out, void *v_out, int B,
                           int Hkv, int N, int budget, int row_bytes, hipStream_t stream) {

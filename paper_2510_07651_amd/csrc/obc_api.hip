@@ -147,4 +147,11 @@ int obc_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_o
     return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
 }
 
+int obc_probe_read_bandwidth(const void *buf, size_t bytes, uint32_t *sink, void *hip_stream) {
+    if (!buf || !sink || bytes < 16 || bytes % 16 != 0) return OBC_EINVAL;
+    if (((uintptr_t)buf & 15) != 0) return OBC_EINVAL;
+    const hipError_t e = launch_stream_read(buf, bytes, sink, OBC_PROBE_BLOCKS, (hipStream_t)hip_stream);
+    return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
+}
+
 }  // extern "C"
