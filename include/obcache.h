@@ -125,7 +125,24 @@ int obc_select(const float *scores, int budget, int32_t *keep_idx,
                int B, int Hkv, int N, const int32_t *seq_lens_host, void *hip_stream);
 
 /*
- * Compaction (Algorithm 2's gather, without the recent-window tail):
+ * Selection with protected regions (Appendix E, Algorithm 2: only positions below
+ * cutoff = len_b - num_recent + num_coming compete for the num_hh heavy-hitter slots and
+ * the tail [cutoff, len_b) is always kept; Appendix C, decoding setup: the first tokens are
+ * always kept as attention sinks).  Per (b, KV head) the kept set is
+ *   {0 .. num_sinks-1}  +  the num_hh highest scores among num_sinks <= p < cutoff
+ *   (ties: lowest index)  +  {cutoff .. len_b-1},
+ * written ascending to keep_idx [B, Hkv, num_sinks + num_hh + num_recent - num_coming];
+ * obc_compact with these indices yields Algorithm 2's [heavy hitters ; recent rows].
+ * num_sinks = num_recent = num_coming = 0 is obc_select.  Requires
+ * 0 <= num_coming <= num_recent, num_hh >= 0, num_sinks >= 0, a non-empty kept set, and
+ * num_sinks + num_hh <= cutoff for every sequence.  Scores and ordering as in obc_select.
+ */
+int obc_select_protected(const float *scores, int num_hh, int num_sinks, int num_recent, int num_coming,
+                         int32_t *keep_idx, int B, int Hkv, int N, const int32_t *seq_lens_host,
+                         void *hip_stream);
+
+/*
+ * Compaction (Algorithm 2's gather; with indices from obc_select_protected the recent rows come along):
  *   k_out[b,g,j,:] = k[b,g,keep_idx[b,g,j],:]   and the same for v.
  *   k, v          [B, Hkv, N, d] of `dtype`
  *   keep_idx      [B, Hkv, budget] int32, every entry in [0, N)  (device; not

@@ -11,5 +11,6 @@ from .binding import (  # noqa: F401
     num_threads,
     score,
     select,
+    select_protected,
     window_attention,
 )

@@ -52,6 +52,8 @@ def _load():
         lib.obc_oracle_attn_score.argtypes = [dp, dp, dp] + [c_int] * 6 + [ip, dp]
         lib.obc_oracle_select.restype = c_int
         lib.obc_oracle_select.argtypes = [fp, c_int, c_int, c_int, c_int, ip, ip]
+        lib.obc_oracle_select_protected.restype = c_int
+        lib.obc_oracle_select_protected.argtypes = [fp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, ip, ip]
         lib.obc_oracle_compact.restype = c_int
         lib.obc_oracle_compact.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ip, c_int, c_int, c_int, c_int,
                                            ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
@@ -142,6 +144,23 @@ def select(scores, budget: int, seq_lens=None):
     rc = _load().obc_oracle_select(s.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), B, Hkv, N, int(budget), lp,
                                    out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
     _check(rc, "select")
+    return out
+
+
+def select_protected(scores, num_hh: int, num_sinks: int = 0, num_recent: int = 0, num_coming: int = 0,
+                     seq_lens=None):
+    """keep_idx [B,Hkv,num_sinks+num_hh+num_recent-num_coming] int32 ascending (Algorithm 2 with sinks)."""
+    if hasattr(scores, "detach"):
+        scores = scores.detach().cpu().numpy()
+    s = np.ascontiguousarray(scores, dtype=np.float32)
+    B, Hkv, N = s.shape
+    keep, lp = _lens(seq_lens, B)
+    total = int(num_sinks) + int(num_hh) + int(num_recent) - int(num_coming)
+    out = np.empty((B, Hkv, max(total, 0)), dtype=np.int32)
+    rc = _load().obc_oracle_select_protected(s.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), B, Hkv, N,
+                                             int(num_hh), int(num_sinks), int(num_recent), int(num_coming), lp,
+                                             out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    _check(rc, "select_protected")
     return out
 
 

@@ -307,6 +307,52 @@ int obc_oracle_select(const float *scores, int B, int Hkv, int N, int budget,
 }
 
 /*
+ * Selection with protected regions (Appendix E, Algorithm 2; Appendix C, decoding setup).
+ * Algorithm 2 lets only positions below cutoff = len - num_recent + num_coming compete
+ * for the num_hh heavy-hitter slots and always keeps the tail [cutoff, len); the
+ * decoding experiments additionally always keep the first few tokens as attention
+ * sinks.  Per (b, g):
+ *   kept = {0 .. num_sinks-1}
+ *        + the num_hh highest scores among p in [num_sinks, cutoff)  (ties: lowest index)
+ *        + {cutoff .. len-1},
+ * written in ascending order; keep_idx is [B, Hkv, num_sinks + num_hh + num_recent - num_coming].
+ * With num_sinks = 0 this is Algorithm 2 literally (topk over S[..., :cutoff], sort, then
+ * the recent rows appended); with num_recent = num_coming as well it is obc_oracle_select.
+ */
+int obc_oracle_select_protected(const float *scores, int B, int Hkv, int N, int num_hh, int num_sinks,
+                                int num_recent, int num_coming, const int32_t *seq_lens, int32_t *keep_idx)
+{
+    if (B < 1 || Hkv < 1 || N < 1 || num_hh < 0 || num_sinks < 0 || num_coming < 0 || num_recent < num_coming)
+        return OBC_ORACLE_EINVAL;
+    const int tail = num_recent - num_coming, total = num_sinks + num_hh + tail;
+    if (total < 1) return OBC_ORACLE_EINVAL;
+    for (int b = 0; b < B; ++b) {
+        int len = seq_len_of(seq_lens, b, N);
+        if (len > N || len - tail < num_sinks + num_hh) return OBC_ORACLE_EINVAL;
+    }
+    scored_t *tmp = (scored_t *)malloc(sizeof(scored_t) * (size_t)N);
+    for (int bg = 0; bg < B * Hkv; ++bg) {
+        const int len = seq_len_of(seq_lens, bg / Hkv, N);
+        const int cutoff = len - tail;
+        int32_t *out = keep_idx + (size_t)bg * total;
+        int n = 0;
+        for (int p = 0; p < num_sinks; ++p) out[n++] = p;
+        int m = 0;
+        for (int p = num_sinks; p < cutoff; ++p) {
+            tmp[m].s = scores[(size_t)bg * N + p];
+            tmp[m].p = p;
+            ++m;
+        }
+        qsort(tmp, (size_t)m, sizeof(scored_t), cmp_scored);
+        for (int j = 0; j < num_hh; ++j) out[n++] = tmp[j].p;
+        qsort(out + num_sinks, (size_t)num_hh, sizeof(int32_t), cmp_i32);
+        for (int p = cutoff; p < len; ++p) out[n++] = p;
+    }
+    free(tmp);
+    return OBC_ORACLE_OK;
+}
+
+/*
  * Row gather (Algorithm 2 without the recent-window tail):
  *   k_out[b,g,j,:] = k[b,g,keep_idx[b,g,j],:], same for v.  Rows are
  *   row_bytes = d * element size bytes long.

@@ -53,6 +53,9 @@ def load_library():
     lib.obc_score_stages.argtypes = lib.obc_score.argtypes + [c_int]
     lib.obc_select.restype = c_int
     lib.obc_select.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int, i32p, c_void_p]
+    lib.obc_select_protected.restype = c_int
+    lib.obc_select_protected.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_int, c_int, c_int, i32p,
+                                         c_void_p]
     lib.obc_compact.restype = c_int
     lib.obc_compact.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int,
                                 c_int, c_void_p]
@@ -147,10 +150,32 @@ def obc_select(scores: torch.Tensor, budget: int, seq_lens=None,
     B, Hkv, N = scores.shape
     if keep_idx is None:
         keep_idx = torch.empty((B, Hkv, max(int(budget), 0)), dtype=torch.int32, device=scores.device)
+    elif keep_idx.dtype != torch.int32 or tuple(keep_idx.shape) != (B, Hkv, int(budget)) or not keep_idx.is_contiguous():
+        raise ValueError("keep_idx must be a contiguous [B,Hkv,%d] int32 tensor" % int(budget))
     rc = load_library().obc_select(scores.data_ptr(), int(budget), keep_idx.data_ptr(), B, Hkv, N,
                                    _lens_arg(seq_lens, B), _stream_ptr(scores))
     if rc != OBC_OK:
         raise ObcError(rc, "obc_select")
+    return keep_idx
+
+
+def obc_select_protected(scores: torch.Tensor, num_hh: int, num_sinks: int = 0, num_recent: int = 0,
+                         num_coming: int = 0, seq_lens=None, keep_idx: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """scores [B,Hkv,N] fp32 -> keep_idx [B,Hkv,num_sinks+num_hh+num_recent-num_coming] int32 ascending."""
+    _require_cuda(scores)
+    if scores.dtype != torch.float32 or scores.dim() != 3:
+        raise ValueError("scores must be [B,Hkv,N] float32")
+    B, Hkv, N = scores.shape
+    total = int(num_sinks) + int(num_hh) + int(num_recent) - int(num_coming)
+    if keep_idx is None:
+        keep_idx = torch.empty((B, Hkv, max(total, 0)), dtype=torch.int32, device=scores.device)
+    elif keep_idx.dtype != torch.int32 or tuple(keep_idx.shape) != (B, Hkv, total) or not keep_idx.is_contiguous():
+        raise ValueError("keep_idx must be a contiguous [B,Hkv,%d] int32 tensor" % total)
+    rc = load_library().obc_select_protected(scores.data_ptr(), int(num_hh), int(num_sinks), int(num_recent),
+                                             int(num_coming), keep_idx.data_ptr(), B, Hkv, N,
+                                             _lens_arg(seq_lens, B), _stream_ptr(scores))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_select_protected")
     return keep_idx
 
 

@@ -9,6 +9,12 @@
 // budget is filled -- which is both the lowest-index tie-break and the ascending output
 // order.  Integer-only bookkeeping: results are exact and reproducible.
 //
+// Protected regions (Appendix E, Algorithm 2: only positions below the cutoff compete and the
+// recent tail is always kept; Appendix C: leading attention-sink tokens are always kept):
+// tokens p < first or p >= len - tail get the key 0xffffffff, which no score maps to, so
+// they outrank every competitor and the same select keeps them all when the budget is
+// first + heavy hitters + tail.
+//
 // Heads of up to 65536 tokens are read from memory once (128-bit loads) and their keys
 // stay in registers for all passes; longer heads are streamed again in every pass.
 #include "internal.h"
@@ -125,7 +131,7 @@ __device__ __forceinline__ void emit_chunk(SelectShared &sh, const uint32_t (&ke
 // Keys of chunks c0 .. c0 + kRegChunks - 1 of one head (128-bit loads where possible).
 template <int kRegChunks>
 __device__ __forceinline__ void load_batch(uint32_t (&keys)[kRegChunks][kItems], const float *__restrict__ s, int c0,
-                                           int n_chunks, int len, bool vec_ok) {
+                                           int n_chunks, int len, bool vec_ok, int first, int cutoff) {
 #pragma unroll
     for (int c = 0; c < kRegChunks; ++c) {
         if (c0 + c < n_chunks) {                          // uniform
@@ -138,6 +144,11 @@ __device__ __forceinline__ void load_batch(uint32_t (&keys)[kRegChunks][kItems],
 #pragma unroll
                 for (int e = 0; e < kItems; ++e) keys[c][e] = i0 + e < len ? order_key(s[i0 + e]) : 0u;
             }
+            if (i0 < first || i0 + kItems > cutoff) {     // some of these tokens are protected
+#pragma unroll
+                for (int e = 0; e < kItems; ++e)
+                    if (i0 + e < first || (i0 + e >= cutoff && i0 + e < len)) keys[c][e] = 0xffffffffu;
+            }
         }
     }
 }
@@ -147,11 +158,12 @@ __device__ __forceinline__ void load_batch(uint32_t (&keys)[kRegChunks][kItems],
 // chunks (all loads of a batch are issued before any is used).
 template <int kRegChunks, bool kResident>
 __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restrict__ scores, int N, int budget,
-                                                           int Hkv, int ragged, SeqLens lens,
+                                                           int Hkv, int ragged, SeqLens lens, int first, int tail,
                                                            int32_t *__restrict__ keep_idx) {
     __shared__ SelectShared sh;
     const int bg = blockIdx.x;
     const int len = seq_len_of(lens, ragged, bg / Hkv, N);
+    const int cutoff = len - tail;                        // tokens at or beyond it are always kept
     const float *s = scores + (size_t)bg * N;
     int32_t *out = keep_idx + (size_t)bg * budget;
     const int tid = threadIdx.x;
@@ -163,7 +175,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
     for (int c = 0; c < kRegChunks; ++c)
 #pragma unroll
         for (int e = 0; e < kItems; ++e) keys[c][e] = 0u;
-    if (kResident) load_batch<kRegChunks>(keys, s, 0, n_chunks, len, vec_ok);
+    if (kResident) load_batch<kRegChunks>(keys, s, 0, n_chunks, len, vec_ok, first, cutoff);
 
     // ---- radix select: key of the budget-th largest element ----
     uint32_t prefix = 0, mask = 0;
@@ -187,7 +199,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
             }
         } else {
             for (int c0 = 0; c0 < n_chunks; c0 += kRegChunks) {
-                load_batch<kRegChunks>(keys, s, c0, n_chunks, len, vec_ok);
+                load_batch<kRegChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff);
 #pragma unroll
                 for (int c = 0; c < kRegChunks; ++c) {
                     if (c0 + c < n_chunks) {              // uniform
@@ -217,7 +229,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
                 emit_chunk(sh, keys[c], c * kChunk + tid * kItems, len, thr, need_eq, budget, gt_base, eq_base, out);
     } else {
         for (int c0 = 0; c0 < n_chunks; c0 += kRegChunks) {
-            load_batch<kRegChunks>(keys, s, c0, n_chunks, len, vec_ok);
+            load_batch<kRegChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff);
 #pragma unroll
             for (int c = 0; c < kRegChunks; ++c)
                 if (c0 + c < n_chunks)
@@ -229,14 +241,14 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
 }  // namespace
 
 hipError_t launch_select(const float *scores, int budget, int32_t *keep_idx, int B, int Hkv, int N, int ragged,
-                         const SeqLens &lens, hipStream_t stream) {
+                         const SeqLens &lens, int first, int tail, hipStream_t stream) {
     const dim3 grid(B * Hkv), block(kSelThreads);
     if (N <= 8 * kChunk)
-        select_topk<8, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, keep_idx);
+        select_topk<8, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, keep_idx);
     else if (N <= 16 * kChunk)
-        select_topk<16, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, keep_idx);
+        select_topk<16, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, keep_idx);
     else
-        select_topk<8, false><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, keep_idx);
+        select_topk<8, false><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, keep_idx);
     return hipGetLastError();
 }
 

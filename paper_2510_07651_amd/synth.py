@@ -154,4 +154,9 @@ def small_cases() -> List[Workload]:
                  sinks=1, ragged=(8, 300), pad_nan=True),
         Workload("s_bf16_d64", B=2, Hq=4, Hkv=2, d=64, N=500, W=16, dtype="bf16", budget=50, seed=22, sinks=2),
         Workload("s_fp32_d128_w64", B=1, Hq=2, Hkv=1, d=128, N=260, W=64, dtype="fp32", budget=65, seed=23, sinks=1),
+        # the largest shapes the library accepts: 512 window rows per KV head (G=8, W=64), 128 ragged sequences
+        Workload("s_bf16_max_rows", B=1, Hq=8, Hkv=1, d=128, N=500, W=64, dtype="bf16", budget=100, seed=24,
+                 sinks=2, outlier_channels=4),
+        Workload("s_bf16_max_batch", B=128, Hq=2, Hkv=1, d=128, N=96, W=4, dtype="bf16", budget=4, seed=25,
+                 ragged=(4, 96), pad_nan=True),
     ]

@@ -82,6 +82,17 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     short = (ctypes.c_int32 * 1)(3)
     assert sel(fake, 4, fake, 1, 1, 16, short, None) == obc.OBC_EINVAL          # budget > len_b
 
+    sp = lib.obc_select_protected          # (scores, num_hh, num_sinks, num_recent, num_coming, keep, B, Hkv, N, lens, stream)
+    assert sp(None, 4, 0, 0, 0, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
+    assert sp(fake, 4, 0, 2, 3, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL         # num_coming > num_recent
+    assert sp(fake, -1, 0, 0, 0, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
+    assert sp(fake, 0, 0, 0, 0, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL         # nothing kept
+    assert sp(fake, 10, 4, 5, 2, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL        # 17 kept of 16
+    assert sp(fake, 2, 1, 1, 0, fake, 1, 1, 16, short, None) == obc.OBC_EINVAL        # 4 kept of len 3
+    probe = lib.obc_probe_read_bandwidth
+    assert probe(None, 1024, fake, None) == obc.OBC_EINVAL
+    assert probe(fake, 1000, fake, None) == obc.OBC_EINVAL                            # not a multiple of 16
+
     cp = lib.obc_compact
     assert cp(fake, fake, None, fake, fake, 1, 1, 16, 4, 64, 0, None) == obc.OBC_EINVAL
     assert cp(fake, fake, fake, fake, fake, 1, 1, 16, 0, 64, 0, None) == obc.OBC_EINVAL

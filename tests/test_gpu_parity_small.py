@@ -101,6 +101,39 @@ def test_select_crafted_ties_and_specials():
         np.testing.assert_array_equal(keep, oracle.select(s, budget, lens))
 
 
+def test_select_protected_matches_oracle():
+    """Algorithm 2's recent tail and cutoff, plus always-kept sinks: bit-exact indices, then the compacted rows."""
+    dev = torch.device("cuda")
+    rng = np.random.default_rng(6)
+    cases = []
+    s = rng.random((2, 3, 5000)).astype(np.float32)
+    cases.append((s, dict(num_hh=700, num_sinks=4, num_recent=256, num_coming=1), [5000, 3111]))
+    cases.append((s, dict(num_hh=700, num_sinks=0, num_recent=64, num_coming=0), None))
+    cases.append((s, dict(num_hh=40, num_sinks=0, num_recent=0, num_coming=0), None))      # plain select
+    t = np.floor(rng.random((1, 2, 9000)) * 5).astype(np.float32)                          # ties across the cut
+    t[0, 0, :4] = -3.0                                                                     # sinks kept whatever they score
+    t[0, 1, -20:] = np.nan                                                                 # so is the recent tail
+    cases.append((t, dict(num_hh=1000, num_sinks=4, num_recent=20, num_coming=0), None))
+    cases.append((t, dict(num_hh=0, num_sinks=2, num_recent=3, num_coming=1), None))       # no heavy hitters
+    cases.append((t[:, :, :64], dict(num_hh=64 - 4 - 7, num_sinks=4, num_recent=8, num_coming=1), None))  # keep all
+    big = rng.random((1, 2, 100000)).astype(np.float32)                                    # streamed (non-resident) kernel
+    cases.append((big, dict(num_hh=764, num_sinks=4, num_recent=256, num_coming=0), [99000]))
+    for s, kw, lens in cases:
+        keep = obc.obc_select_protected(torch.from_numpy(s).to(dev), seq_lens=lens, **kw).cpu().numpy()
+        np.testing.assert_array_equal(keep, oracle.select_protected(s, seq_lens=lens, **kw))
+    # evict_kv of Algorithm 2 end to end: gather with these indices == [heavy hitters ; recent rows]
+    g = torch.Generator().manual_seed(4)
+    k = torch.randn(2, 3, 5000, 128, generator=g).to(torch.bfloat16); v = torch.randn(2, 3, 5000, 128, generator=g).to(torch.bfloat16)
+    s, kw, lens = cases[0]
+    keep = obc.obc_select_protected(torch.from_numpy(s).to(dev), seq_lens=lens, **kw)
+    ko, vo = obc.obc_compact(k.to(dev), v.to(dev), keep)
+    kref, vref = oracle.compact(k.view(torch.int16).numpy(), v.view(torch.int16).numpy(), keep.cpu().numpy())
+    np.testing.assert_array_equal(ko.view(torch.int16).cpu().numpy(), kref)
+    np.testing.assert_array_equal(vo.view(torch.int16).cpu().numpy(), vref)
+    tail = kw["num_recent"] - kw["num_coming"]
+    assert torch.equal(ko[0, 0, -tail:].cpu(), k[0, 0, 5000 - tail:])                      # the recent rows, in order
+
+
 def test_compact_fp32_and_edge_rows():
     dev = torch.device("cuda")
     g = torch.Generator().manual_seed(3)

@@ -337,3 +337,60 @@ def test_compact_matches_fancy_indexing():
     kf = rng.standard_normal((1, 1, 9, 4)).astype(np.float32)
     ko, _ = oracle.compact(kf, kf, np.array([[[0, 8]]], dtype=np.int32))
     np.testing.assert_array_equal(ko[0, 0], kf[0, 0, [0, 8]])
+
+
+# ---- selection with protected regions (Appendix E, Algorithm 2; sinks as in the decoding setup of Appendix C) ----
+
+def test_select_protected_is_topk_below_cutoff_plus_recent_tail():
+    """Distinct scores: library top-k over S[..., :cutoff], sorted, recent rows appended (Algorithm 2's semantics)."""
+    g = torch.Generator().manual_seed(81)
+    S = torch.rand(2, 3, 200, generator=g)
+    num_hh, num_recent, num_coming = 17, 32, 5
+    cutoff = 200 - num_recent + num_coming
+    hh = torch.topk(S[..., :cutoff], num_hh, dim=-1).indices.sort(dim=-1).values
+    tail = torch.arange(cutoff, 200).expand(2, 3, -1)
+    want = torch.cat([hh, tail], dim=-1).numpy().astype(np.int32)
+    got = oracle.select_protected(S.numpy(), num_hh, 0, num_recent, num_coming)
+    np.testing.assert_array_equal(got, want)
+    # compaction with these indices == gather of the heavy hitters followed by the recent rows
+    k = torch.randn(2, 3, 200, 4, generator=g)
+    ko, _ = oracle.compact(k.numpy(), k.numpy(), got)
+    k_hh = torch.gather(k[..., :cutoff, :], 2, hh.unsqueeze(-1).expand(-1, -1, -1, 4))
+    np.testing.assert_array_equal(ko, torch.cat([k_hh, k[..., cutoff:, :]], dim=2).numpy())
+
+
+def test_select_protected_reduces_to_plain_select():
+    rng = np.random.default_rng(82)
+    s = np.floor(rng.random((2, 2, 300)) * 9).astype(np.float32)         # ties everywhere
+    lens = [300, 123]
+    np.testing.assert_array_equal(oracle.select_protected(s, 40, 0, 0, 0, lens), oracle.select(s, 40, lens))
+    np.testing.assert_array_equal(oracle.select_protected(s, 40, 0, 7, 7, lens), oracle.select(s, 40, lens))
+
+
+def test_select_protected_sinks_ties_and_ragged():
+    rng = np.random.default_rng(83)
+    s = np.floor(rng.random((3, 2, 150)) * 5).astype(np.float32)
+    s[0, 0, :4] = -1.0                                                   # sinks are kept whatever they score
+    lens = [150, 61, 97]
+    num_hh, sinks, recent, coming = 20, 4, 16, 3
+    tail = recent - coming
+    got = oracle.select_protected(s, num_hh, sinks, recent, coming, lens)
+    assert got.shape == (3, 2, sinks + num_hh + tail)
+    for b in range(3):
+        L = lens[b]
+        cutoff = L - tail
+        for h in range(2):
+            row = got[b, h]
+            assert np.all(np.diff(row) > 0)
+            np.testing.assert_array_equal(row[:sinks], np.arange(sinks))
+            np.testing.assert_array_equal(row[-tail:], np.arange(cutoff, L))
+            cand = np.arange(sinks, cutoff)
+            order = cand[np.argsort(-s[b, h, cand].astype(np.float64), kind="stable")]
+            np.testing.assert_array_equal(row[sinks:sinks + num_hh], np.sort(order[:num_hh]))
+    # budget consumes every candidate; no heavy hitters at all
+    np.testing.assert_array_equal(oracle.select_protected(s[:1, :1, :20], 20 - 4 - 5, 4, 5, 0)[0, 0], np.arange(20))
+    np.testing.assert_array_equal(oracle.select_protected(s[:1, :1, :20], 0, 2, 3, 0)[0, 0], [0, 1, 17, 18, 19])
+    with pytest.raises(ValueError):
+        oracle.select_protected(s, 140, 4, 16, 3, lens)                  # does not fit the shortest sequence
+    with pytest.raises(ValueError):
+        oracle.select_protected(s, 5, 0, 2, 3)                           # num_coming > num_recent
