@@ -142,6 +142,21 @@ int obc_select_protected(const float *scores, int num_hh, int num_sinks, int num
                          void *hip_stream);
 
 /*
+ * Pooled selection (Appendix C, "SnapKV": the scores are smoothed by a one-dimensional
+ * average-pooling filter, kernel size 5 in the paper's experiments, before eviction).
+ * Same kept set and output as obc_select_protected, but the competing tokens
+ * num_sinks <= p < cutoff are ranked by the sum of the scores in their centred window of
+ * `pool` positions (stride 1; positions outside the competing range count as zero).  The
+ * sum is taken in fp32 in ascending position order; it ranks tokens as the average does
+ * and involves no division.  `pool` is odd, 1 <= pool <= OBC_MAX_POOL; pool = 1 is
+ * obc_select_protected.  `scores` itself is not modified.
+ */
+#define OBC_MAX_POOL 15
+int obc_select_pooled(const float *scores, int num_hh, int num_sinks, int num_recent, int num_coming, int pool,
+                      int32_t *keep_idx, int B, int Hkv, int N, const int32_t *seq_lens_host,
+                      void *hip_stream);
+
+/*
  * Compaction (Algorithm 2's gather; with indices from obc_select_protected the recent rows come along):
  *   k_out[b,g,j,:] = k[b,g,keep_idx[b,g,j],:]   and the same for v.
  *   k, v          [B, Hkv, N, d] of `dtype`

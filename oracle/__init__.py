@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     num_threads,
     score,
     select,
+    select_pooled,
     select_protected,
     window_attention,
 )

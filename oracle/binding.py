@@ -54,6 +54,8 @@ def _load():
         lib.obc_oracle_select.argtypes = [fp, c_int, c_int, c_int, c_int, ip, ip]
         lib.obc_oracle_select_protected.restype = c_int
         lib.obc_oracle_select_protected.argtypes = [fp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, ip, ip]
+        lib.obc_oracle_select_pooled.restype = c_int
+        lib.obc_oracle_select_pooled.argtypes = [fp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_int, ip, ip]
         lib.obc_oracle_compact.restype = c_int
         lib.obc_oracle_compact.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ip, c_int, c_int, c_int, c_int,
                                            ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
@@ -161,6 +163,23 @@ def select_protected(scores, num_hh: int, num_sinks: int = 0, num_recent: int = 
                                              int(num_hh), int(num_sinks), int(num_recent), int(num_coming), lp,
                                              out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
     _check(rc, "select_protected")
+    return out
+
+
+def select_pooled(scores, num_hh: int, pool: int = 5, num_sinks: int = 0, num_recent: int = 0, num_coming: int = 0,
+                  seq_lens=None):
+    """Like select_protected, with candidates ranked by their centred window sum of `pool` scores (fp32)."""
+    if hasattr(scores, "detach"):
+        scores = scores.detach().cpu().numpy()
+    s = np.ascontiguousarray(scores, dtype=np.float32)
+    B, Hkv, N = s.shape
+    keep, lp = _lens(seq_lens, B)
+    total = int(num_sinks) + int(num_hh) + int(num_recent) - int(num_coming)
+    out = np.empty((B, Hkv, max(total, 0)), dtype=np.int32)
+    rc = _load().obc_oracle_select_pooled(s.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), B, Hkv, N, int(num_hh),
+                                          int(num_sinks), int(num_recent), int(num_coming), int(pool), lp,
+                                          out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    _check(rc, "select_pooled")
     return out
 
 

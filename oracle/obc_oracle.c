@@ -353,6 +353,44 @@ int obc_oracle_select_protected(const float *scores, int B, int Hkv, int N, int 
 }
 
 /*
+ * Pooled selection (Appendix C, "SnapKV": a one-dimensional average-pooling filter of
+ * kernel size 5 smooths the scores before eviction; used for every OBCache-enhanced
+ * prefill experiment).  Same kept set as obc_oracle_select_protected, but the candidates
+ * p in [num_sinks, cutoff) are ranked by the window sum
+ *   P_p = sum_{j = p-r .. p+r, num_sinks <= j < cutoff} S_j ,   r = (pool - 1) / 2,
+ * i.e. a centred stride-1 window with zeros beyond the candidate range.  The average is
+ * P_p / pool; ranking by the sum avoids a division whose rounding could merge distinct
+ * sums.  The sum runs in fp32 in ascending j starting from 0 (out-of-range terms add
+ * +0), because this rounding decides which indices are kept and both sides must take
+ * the decision in the same precision.  pool = 1 is obc_oracle_select_protected.
+ */
+int obc_oracle_select_pooled(const float *scores, int B, int Hkv, int N, int num_hh, int num_sinks,
+                             int num_recent, int num_coming, int pool, const int32_t *seq_lens,
+                             int32_t *keep_idx)
+{
+    if (pool < 1 || pool % 2 == 0 || N < 1 || B < 1 || Hkv < 1) return OBC_ORACLE_EINVAL;
+    if (num_recent < num_coming || num_coming < 0 || num_sinks < 0) return OBC_ORACLE_EINVAL;
+    const int r = (pool - 1) / 2, tail = num_recent - num_coming;
+    float *pooled = (float *)malloc(sizeof(float) * (size_t)B * Hkv * N);
+    for (int bg = 0; bg < B * Hkv; ++bg) {
+        const int len = seq_len_of(seq_lens, bg / Hkv, N);
+        const int cutoff = len - tail;
+        const float *s = scores + (size_t)bg * N;
+        float *o = pooled + (size_t)bg * N;
+        for (int p = 0; p < N; ++p) {
+            volatile float sum = 0.0f;          /* volatile: every partial sum is rounded to fp32 */
+            if (p >= num_sinks && p < cutoff)
+                for (int j = p - r; j <= p + r; ++j) sum = sum + ((j >= num_sinks && j < cutoff) ? s[j] : 0.0f);
+            o[p] = sum;
+        }
+    }
+    const int rc = obc_oracle_select_protected(pooled, B, Hkv, N, num_hh, num_sinks, num_recent, num_coming,
+                                               seq_lens, keep_idx);
+    free(pooled);
+    return rc;
+}
+
+/*
  * Row gather (Algorithm 2 without the recent-window tail):
  *   k_out[b,g,j,:] = k[b,g,keep_idx[b,g,j],:], same for v.  Rows are
  *   row_bytes = d * element size bytes long.

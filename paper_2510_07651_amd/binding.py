@@ -56,6 +56,9 @@ def load_library():
     lib.obc_select_protected.restype = c_int
     lib.obc_select_protected.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_int, c_int, c_int, i32p,
                                          c_void_p]
+    lib.obc_select_pooled.restype = c_int
+    lib.obc_select_pooled.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_int, c_int, c_int, i32p,
+                                      c_void_p]
     lib.obc_compact.restype = c_int
     lib.obc_compact.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int,
                                 c_int, c_void_p]
@@ -176,6 +179,26 @@ def obc_select_protected(scores: torch.Tensor, num_hh: int, num_sinks: int = 0, 
                                              _lens_arg(seq_lens, B), _stream_ptr(scores))
     if rc != OBC_OK:
         raise ObcError(rc, "obc_select_protected")
+    return keep_idx
+
+
+def obc_select_pooled(scores: torch.Tensor, num_hh: int, pool: int = 5, num_sinks: int = 0, num_recent: int = 0,
+                      num_coming: int = 0, seq_lens=None, keep_idx: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Like obc_select_protected, competitors ranked by their centred window sum of `pool` scores."""
+    _require_cuda(scores)
+    if scores.dtype != torch.float32 or scores.dim() != 3:
+        raise ValueError("scores must be [B,Hkv,N] float32")
+    B, Hkv, N = scores.shape
+    total = int(num_sinks) + int(num_hh) + int(num_recent) - int(num_coming)
+    if keep_idx is None:
+        keep_idx = torch.empty((B, Hkv, max(total, 0)), dtype=torch.int32, device=scores.device)
+    elif keep_idx.dtype != torch.int32 or tuple(keep_idx.shape) != (B, Hkv, total) or not keep_idx.is_contiguous():
+        raise ValueError("keep_idx must be a contiguous [B,Hkv,%d] int32 tensor" % total)
+    rc = load_library().obc_select_pooled(scores.data_ptr(), int(num_hh), int(num_sinks), int(num_recent),
+                                          int(num_coming), int(pool), keep_idx.data_ptr(), B, Hkv, N,
+                                          _lens_arg(seq_lens, B), _stream_ptr(scores))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_select_pooled")
     return keep_idx
 
 

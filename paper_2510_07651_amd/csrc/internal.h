@@ -58,7 +58,7 @@ void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWo
 hipError_t launch_score_plain(const ScoreArgs &a, const ScoreWorkspace &ws, char *ws_base, hipStream_t stream);
 hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char *ws_base, hipStream_t stream);
 hipError_t launch_select(const float *scores, int budget, int32_t *keep_idx, int B, int Hkv, int N, int ragged,
-                         const SeqLens &lens, int first, int tail, hipStream_t stream);
+                         const SeqLens &lens, int first, int tail, int radius, hipStream_t stream);
 hipError_t launch_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_out, void *v_out, int B,
                           int Hkv, int N, int budget, int row_bytes, hipStream_t stream);
 hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int blocks, hipStream_t stream);

@@ -15,6 +15,12 @@
 // they outrank every competitor and the same select keeps them all when the budget is
 // first + heavy hitters + tail.
 //
+// Pooling (Appendix C, SnapKV paragraph: average pooling of the scores, kernel size 5, before
+// eviction): with radius r > 0 a competing token is ranked by the fp32 sum of the scores in
+// its centred window of 2r+1 positions, taken in ascending position order, positions
+// outside the competing range counting as zero.  The sum orders tokens as the average does
+// and needs no division.
+//
 // Heads of up to 65536 tokens are read from memory once (128-bit loads) and their keys
 // stay in registers for all passes; longer heads are streamed again in every pass.
 #include "internal.h"
@@ -37,6 +43,7 @@ __device__ __forceinline__ uint32_t order_key(float f) {
 }
 
 constexpr int kBins = 2048;
+constexpr int kMaxRadius = 7;                           // largest pooling window: 15 scores
 
 struct SelectShared {
     int hist[kBins];
@@ -131,12 +138,28 @@ __device__ __forceinline__ void emit_chunk(SelectShared &sh, const uint32_t (&ke
 // Keys of chunks c0 .. c0 + kRegChunks - 1 of one head (128-bit loads where possible).
 template <int kRegChunks>
 __device__ __forceinline__ void load_batch(uint32_t (&keys)[kRegChunks][kItems], const float *__restrict__ s, int c0,
-                                           int n_chunks, int len, bool vec_ok, int first, int cutoff) {
+                                           int n_chunks, int len, bool vec_ok, int first, int cutoff, int radius) {
 #pragma unroll
     for (int c = 0; c < kRegChunks; ++c) {
         if (c0 + c < n_chunks) {                          // uniform
             const int i0 = (c0 + c) * kChunk + (int)threadIdx.x * kItems;
-            if (vec_ok && i0 + kItems <= len) {
+            if (radius > 0) {                             // uniform: pooled ranking
+                float w[kItems + 2 * kMaxRadius];
+#pragma unroll
+                for (int j = 0; j < kItems + 2 * kMaxRadius; ++j) {
+                    const int idx = i0 - radius + j;
+                    const bool ok = j < kItems + 2 * radius && idx >= first && idx < cutoff;
+                    w[j] = ok ? s[idx] : 0.f;
+                }
+#pragma unroll
+                for (int e = 0; e < kItems; ++e) {
+                    float sum = w[e];
+#pragma unroll
+                    for (int j = 1; j <= 2 * kMaxRadius; ++j)
+                        if (j <= 2 * radius) sum = __fadd_rn(sum, w[e + j]);
+                    keys[c][e] = i0 + e < len ? order_key(sum) : 0u;
+                }
+            } else if (vec_ok && i0 + kItems <= len) {
                 const float4 f = *(const float4 *)(s + i0);
                 keys[c][0] = order_key(f.x); keys[c][1] = order_key(f.y);
                 keys[c][2] = order_key(f.z); keys[c][3] = order_key(f.w);
@@ -159,7 +182,7 @@ __device__ __forceinline__ void load_batch(uint32_t (&keys)[kRegChunks][kItems],
 template <int kRegChunks, bool kResident>
 __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restrict__ scores, int N, int budget,
                                                            int Hkv, int ragged, SeqLens lens, int first, int tail,
-                                                           int32_t *__restrict__ keep_idx) {
+                                                           int radius, int32_t *__restrict__ keep_idx) {
     __shared__ SelectShared sh;
     const int bg = blockIdx.x;
     const int len = seq_len_of(lens, ragged, bg / Hkv, N);
@@ -175,7 +198,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
     for (int c = 0; c < kRegChunks; ++c)
 #pragma unroll
         for (int e = 0; e < kItems; ++e) keys[c][e] = 0u;
-    if (kResident) load_batch<kRegChunks>(keys, s, 0, n_chunks, len, vec_ok, first, cutoff);
+    if (kResident) load_batch<kRegChunks>(keys, s, 0, n_chunks, len, vec_ok, first, cutoff, radius);
 
     // ---- radix select: key of the budget-th largest element ----
     uint32_t prefix = 0, mask = 0;
@@ -199,7 +222,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
             }
         } else {
             for (int c0 = 0; c0 < n_chunks; c0 += kRegChunks) {
-                load_batch<kRegChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff);
+                load_batch<kRegChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff, radius);
 #pragma unroll
                 for (int c = 0; c < kRegChunks; ++c) {
                     if (c0 + c < n_chunks) {              // uniform
@@ -229,7 +252,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
                 emit_chunk(sh, keys[c], c * kChunk + tid * kItems, len, thr, need_eq, budget, gt_base, eq_base, out);
     } else {
         for (int c0 = 0; c0 < n_chunks; c0 += kRegChunks) {
-            load_batch<kRegChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff);
+            load_batch<kRegChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff, radius);
 #pragma unroll
             for (int c = 0; c < kRegChunks; ++c)
                 if (c0 + c < n_chunks)
@@ -241,14 +264,14 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
 }  // namespace
 
 hipError_t launch_select(const float *scores, int budget, int32_t *keep_idx, int B, int Hkv, int N, int ragged,
-                         const SeqLens &lens, int first, int tail, hipStream_t stream) {
+                         const SeqLens &lens, int first, int tail, int radius, hipStream_t stream) {
     const dim3 grid(B * Hkv), block(kSelThreads);
     if (N <= 8 * kChunk)
-        select_topk<8, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, keep_idx);
+        select_topk<8, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, radius, keep_idx);
     else if (N <= 16 * kChunk)
-        select_topk<16, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, keep_idx);
+        select_topk<16, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, radius, keep_idx);
     else
-        select_topk<8, false><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, keep_idx);
+        select_topk<8, false><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, radius, keep_idx);
     return hipGetLastError();
 }
 

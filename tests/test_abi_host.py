@@ -89,6 +89,11 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     assert sp(fake, 0, 0, 0, 0, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL         # nothing kept
     assert sp(fake, 10, 4, 5, 2, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL        # 17 kept of 16
     assert sp(fake, 2, 1, 1, 0, fake, 1, 1, 16, short, None) == obc.OBC_EINVAL        # 4 kept of len 3
+    pl = lib.obc_select_pooled             # (scores, num_hh, num_sinks, num_recent, num_coming, pool, keep, B, Hkv, N, lens, stream)
+    assert pl(fake, 4, 0, 0, 0, 4, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL      # even window
+    assert pl(fake, 4, 0, 0, 0, 0, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
+    assert pl(fake, 4, 0, 0, 0, 17, fake, 1, 1, 16, None, None) == obc.OBC_EUNSUPPORTED
+    assert pl(fake, 17, 0, 0, 0, 5, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
     probe = lib.obc_probe_read_bandwidth
     assert probe(None, 1024, fake, None) == obc.OBC_EINVAL
     assert probe(fake, 1000, fake, None) == obc.OBC_EINVAL                            # not a multiple of 16

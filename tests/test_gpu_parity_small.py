@@ -134,6 +134,27 @@ def test_select_protected_matches_oracle():
     assert torch.equal(ko[0, 0, -tail:].cpu(), k[0, 0, 5000 - tail:])                      # the recent rows, in order
 
 
+def test_select_pooled_matches_oracle():
+    """Average-pooled ranking (window sums in fp32, fixed order): indices bit-exact against the oracle."""
+    dev = torch.device("cuda")
+    rng = np.random.default_rng(7)
+    s = (rng.random((2, 3, 6000)).astype(np.float32)) ** 6                 # spread over many binades: sums do round
+    s[0, 0, 100:140] = np.nan                                              # NaN poisons its neighbours' windows on both sides alike
+    big = rng.random((1, 1, 70001)).astype(np.float32)                     # streamed kernel, odd length (scalar tail loads)
+    cases = [
+        (s, dict(num_hh=600, pool=5), None),
+        (s, dict(num_hh=600, pool=5, num_sinks=4, num_recent=64, num_coming=0), [6000, 2501]),
+        (s, dict(num_hh=50, pool=3, num_sinks=1, num_recent=7, num_coming=2), [5999, 64]),
+        (s, dict(num_hh=333, pool=15), None),
+        (s, dict(num_hh=333, pool=1, num_sinks=2, num_recent=5), None),
+        (np.floor(s * 50).astype(np.float32), dict(num_hh=777, pool=7), None),   # heavy ties
+        (big, dict(num_hh=4096, pool=5, num_sinks=4, num_recent=64), None),
+    ]
+    for s_, kw, lens in cases:
+        keep = obc.obc_select_pooled(torch.from_numpy(s_).to(dev), seq_lens=lens, **kw).cpu().numpy()
+        np.testing.assert_array_equal(keep, oracle.select_pooled(s_, seq_lens=lens, **kw))
+
+
 def test_compact_fp32_and_edge_rows():
     dev = torch.device("cuda")
     g = torch.Generator().manual_seed(3)

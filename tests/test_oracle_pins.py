@@ -394,3 +394,34 @@ def test_select_protected_sinks_ties_and_ragged():
         oracle.select_protected(s, 140, 4, 16, 3, lens)                  # does not fit the shortest sequence
     with pytest.raises(ValueError):
         oracle.select_protected(s, 5, 0, 2, 3)                           # num_coming > num_recent
+
+
+# ---- pooled selection (Appendix C, SnapKV paragraph: average pooling, kernel size 5, before eviction) ----
+
+def test_select_pooled_matches_library_avg_pool():
+    """Scores that are small integers: every window sum is exact, so the library's average pooling
+    (zero padding, stride 1) followed by the pinned select must give the same indices."""
+    g = torch.Generator().manual_seed(84)
+    S = torch.randint(0, 1000, (2, 3, 400), generator=g).to(torch.float32)
+    for pool in (3, 5, 7):
+        pooled = torch.nn.functional.avg_pool1d(S.double(), kernel_size=pool, stride=1, padding=pool // 2) * pool
+        want = oracle.select(pooled.to(torch.float32).numpy(), 60)
+        np.testing.assert_array_equal(oracle.select_pooled(S.numpy(), 60, pool=pool), want)
+    np.testing.assert_array_equal(oracle.select_pooled(S.numpy(), 60, pool=1), oracle.select(S.numpy(), 60))
+
+
+def test_select_pooled_window_stays_inside_candidates_and_hand_case():
+    s = np.zeros((1, 1, 12), dtype=np.float32)
+    s[0, 0, [0, 1]] = 100.0          # sinks: huge, but outside the candidate range -> must not leak into token 2
+    s[0, 0, 5] = 9.0                 # window sums (pool 3): tokens 4,5,6 -> 9 each; token 5's neighbours tie with it
+    s[0, 0, [10, 11]] = 50.0         # recent tail: always kept, must not leak into token 9
+    got = oracle.select_pooled(s, 2, pool=3, num_sinks=2, num_recent=2, num_coming=0)[0, 0]
+    np.testing.assert_array_equal(got, [0, 1, 4, 5, 10, 11])     # ties 4,5,6 -> lowest indices
+    # ragged: the window also stops at the true length
+    t = np.zeros((2, 1, 10), dtype=np.float32)
+    t[1, 0, 6] = 5.0                 # beyond len 6 of sequence 1: never read
+    t[:, 0, 2] = 1.0
+    got = oracle.select_pooled(t, 3, pool=5, seq_lens=[10, 6])
+    np.testing.assert_array_equal(got[1, 0], [0, 1, 2])          # sums: p0..p4 = 1, p5 = 0
+    with pytest.raises(ValueError):
+        oracle.select_pooled(t, 3, pool=4)
