@@ -94,6 +94,20 @@ int obc_score(const void *q, const void *k, const void *v,
               void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Decoding-time accumulation (Section 4.2, closing remark: during decoding the scores are
+ * accumulated over time; Appendix C, decoding setup: an eviction decision at every step).
+ * Same arguments as obc_score, but the scores of this call are ADDED to what `scores`
+ * already holds: scores[b,g,p] += S_p for p < len_b, and positions p >= len_b are left
+ * untouched (they belong to tokens that do not exist yet).  A decode step passes the new
+ * token's query with W = 1 and len_b = its position + 1; by Eq. 9 the score of a W-row
+ * window equals the sum of the W single-row calls with growing length.
+ */
+int obc_score_accumulate(const void *q, const void *k, const void *v,
+                         int N, int W, int Hq, int Hkv, int d, int variant, float *scores,
+                         int B, int dtype, const int32_t *seq_lens_host,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Measurement hook: obc_score restricted to some of its stages, so that each kernel
  * of the two-sweep scoring path can be timed on its own with events around the call.
  * Same arguments and checks as obc_score; `stage_mask` is a bit set of

@@ -49,6 +49,8 @@ def load_library():
     lib.obc_score.restype = c_int
     lib.obc_score.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p,
                               c_int, c_int, i32p, c_void_p, c_size_t, c_void_p]
+    lib.obc_score_accumulate.restype = c_int
+    lib.obc_score_accumulate.argtypes = lib.obc_score.argtypes
     lib.obc_score_stages.restype = c_int
     lib.obc_score_stages.argtypes = lib.obc_score.argtypes + [c_int]
     lib.obc_select.restype = c_int
@@ -115,10 +117,11 @@ OBC_STAGE_SWEEP1, OBC_STAGE_COMBINE, OBC_STAGE_SWEEP2, OBC_STAGE_ALL = 1, 2, 4, 
 
 def obc_score(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, variant="joint", seq_lens=None,
               scores: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-              stage_mask: Optional[int] = None) -> torch.Tensor:
+              stage_mask: Optional[int] = None, accumulate: bool = False) -> torch.Tensor:
     """q [B,Hq,W,d], k,v [B,Hkv,N,d] -> scores [B,Hkv,N] fp32 ([3,B,Hkv,N] for variant "all").
 
-    stage_mask (measurement hook) routes the call through obc_score_stages."""
+    stage_mask (measurement hook) routes the call through obc_score_stages; accumulate=True through
+    obc_score_accumulate (adds to the `scores` passed in, which is then required)."""
     _require_cuda(q, k, v)
     B, Hq, W, d = q.shape
     Bk, Hkv, N, dk = k.shape
@@ -129,13 +132,21 @@ def obc_score(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, variant="joint"
     if workspace is None:
         workspace = torch.empty(obc_score_workspace_bytes(B, N, W, Hq, Hkv, d, dt, var), dtype=torch.uint8,
                                 device=q.device)
+    shape = (3, B, Hkv, N) if var == OBC_ALL else (B, Hkv, N)
     if scores is None:
-        shape = (3, B, Hkv, N) if var == OBC_ALL else (B, Hkv, N)
+        if accumulate:
+            raise ValueError("accumulate=True needs the running scores tensor")
         scores = torch.empty(shape, dtype=torch.float32, device=q.device)
+    elif tuple(scores.shape) != shape or scores.dtype != torch.float32 or not scores.is_contiguous():
+        raise ValueError("scores must be a contiguous float32 tensor of shape %s" % (shape,))
     _require_cuda(scores, workspace)
     args = (q.data_ptr(), k.data_ptr(), v.data_ptr(), N, W, Hq, Hkv, d, var, scores.data_ptr(), B, dt,
             _lens_arg(seq_lens, B), workspace.data_ptr(), workspace.numel(), _stream_ptr(q))
-    if stage_mask is None:
+    if accumulate:
+        if stage_mask is not None:
+            raise ValueError("stage_mask and accumulate exclude each other")
+        rc = load_library().obc_score_accumulate(*args)
+    elif stage_mask is None:
         rc = load_library().obc_score(*args)
     else:
         rc = load_library().obc_score_stages(*args, int(stage_mask))

@@ -23,6 +23,7 @@ struct ScoreArgs {
     int dtype;        // obc_dtype_t
     int ragged;       // 0: every sequence has length N
     int stage_mask;   // OBC_STAGE_* bits to run
+    int accumulate;   // 1: add to the scores already in `scores` (positions beyond the true length untouched)
     SeqLens lens;     // valid for b < B when ragged
 };
 

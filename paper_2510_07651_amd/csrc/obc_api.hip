@@ -97,9 +97,27 @@ int obc_score(const void *q, const void *k, const void *v, int N, int W, int Hq,
                             workspace_bytes, hip_stream, OBC_STAGE_ALL);
 }
 
+static int score_impl(const void *q, const void *k, const void *v, int N, int W, int Hq, int Hkv, int d, int variant,
+                      float *scores, int B, int dtype, const int32_t *seq_lens_host, void *workspace,
+                      size_t workspace_bytes, void *hip_stream, int stage_mask, int accumulate);
+
 int obc_score_stages(const void *q, const void *k, const void *v, int N, int W, int Hq, int Hkv, int d, int variant,
                      float *scores, int B, int dtype, const int32_t *seq_lens_host, void *workspace,
                      size_t workspace_bytes, void *hip_stream, int stage_mask) {
+    return score_impl(q, k, v, N, W, Hq, Hkv, d, variant, scores, B, dtype, seq_lens_host, workspace, workspace_bytes,
+                      hip_stream, stage_mask, 0);
+}
+
+int obc_score_accumulate(const void *q, const void *k, const void *v, int N, int W, int Hq, int Hkv, int d,
+                         int variant, float *scores, int B, int dtype, const int32_t *seq_lens_host,
+                         void *workspace, size_t workspace_bytes, void *hip_stream) {
+    return score_impl(q, k, v, N, W, Hq, Hkv, d, variant, scores, B, dtype, seq_lens_host, workspace, workspace_bytes,
+                      hip_stream, OBC_STAGE_ALL, 1);
+}
+
+static int score_impl(const void *q, const void *k, const void *v, int N, int W, int Hq, int Hkv, int d, int variant,
+                      float *scores, int B, int dtype, const int32_t *seq_lens_host, void *workspace,
+                      size_t workspace_bytes, void *hip_stream, int stage_mask, int accumulate) {
     if (!q || !k || !v || !scores) return OBC_EINVAL;
     if (stage_mask < 1 || stage_mask > OBC_STAGE_ALL) return OBC_EINVAL;
     ScoreWorkspace ws;
@@ -115,6 +133,7 @@ int obc_score_stages(const void *q, const void *k, const void *v, int N, int W, 
     a.variant = variant; a.dtype = dtype;
     hipStream_t stream = (hipStream_t)hip_stream;
     a.stage_mask = stage_mask;
+    a.accumulate = accumulate;
     const hipError_t e = ws.use_mfma ? launch_score_mfma(a, ws, (char *)workspace, stream)
                                      : launch_score_plain(a, ws, (char *)workspace, stream);
     return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;

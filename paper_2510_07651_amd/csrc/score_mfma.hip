@@ -803,10 +803,12 @@ struct Sweep2Regs {
 // `tok0`, staged in LDS as [wave][variant][64]) and writes them out; wave c handles variant c.
 template <int kNv>
 __device__ __forceinline__ void sweep2_flush(const float *stage, float *out, size_t variant_stride, int tok0,
-                                             int t_end, int wave, int lane) {
+                                             int t_end, int wave, int lane, bool accumulate) {
     if (wave < kNv && tok0 + lane < t_end) {
         const float *p = stage + wave * 64 + lane;
-        out[wave * variant_stride + tok0 + lane] = (p[0] + p[kNv * 64]) + (p[2 * kNv * 64] + p[3 * kNv * 64]);
+        float *o = out + wave * variant_stride + tok0 + lane;
+        const float sum = (p[0] + p[kNv * 64]) + (p[2 * kNv * 64] + p[3 * kNv * 64]);
+        *o = accumulate ? *o + sum : sum;
     }
 }
 
@@ -821,7 +823,7 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
                                             int t_begin, int t_end, int last_row, const int *vis_i,
                                             const int *excl_i, const char *kh, const char *vh,
                                             const char *const (&kp)[8], const uint32_t (&kdoff)[4], int wave, int lane,
-                                            bool wave_active, float *part, float *out, size_t variant_stride) {
+                                            bool wave_active, float *part, float *out, size_t variant_stride, bool accumulate) {
     constexpr int kNv = kVariant == OBC_ALL ? 3 : 1;
     constexpr bool kDoV = kVariant == OBC_VALUE || kVariant == OBC_ALL;
     constexpr bool kDoK = kVariant == OBC_KEY || kVariant == OBC_ALL;
@@ -841,7 +843,7 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
             tile_load_async<kXor16>(kh, tn, last_row, lds0 + (PH == 0 ? kLdsK1 : kLdsK0), wave, lane, kdoff);
             tile_load_async<kXor16>(vh, tn, last_row, lds0 + (PH == 0 ? kLdsV1 : kLdsV0), wave, lane, kdoff);
         }
-        if (n >= 2) sweep2_flush<kNv>(part + (kSlot ^ 1) * 4 * kNv * 64, out, variant_stride, t_begin + (n - 2) * 32, t_end, wave, lane);
+        if (n >= 2) sweep2_flush<kNv>(part + (kSlot ^ 1) * 4 * kNv * 64, out, variant_stride, t_begin + (n - 2) * 32, t_end, wave, lane, accumulate);
     }
     if (n >= n_blk) return;                                            // uniform
     float acc_v = 0.f, acc_k = 0.f, acc_j = 0.f;
@@ -913,7 +915,8 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
                                                            const float *__restrict__ row_const,
                                                            const float *__restrict__ special,
                                                            float *__restrict__ dst, size_t variant_stride,
-                                                           size_t chunk_stride) {
+                                                           size_t chunk_stride, int accumulate_flag) {
+    const bool accumulate = accumulate_flag != 0;      // add to what `dst` holds; padded positions stay untouched
     constexpr int kNv = kVariant == OBC_ALL ? 3 : 1;
     constexpr bool kNeedVO = kVariant != OBC_VALUE;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -929,6 +932,7 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
     float *out = dst + (size_t)chunk * chunk_stride + (size_t)bg * N;
 
     if (t_begin >= len) {                                      // uniform: only padded positions here
+        if (accumulate) return;
         for (int t = t_begin + threadIdx.x; t < t_stop; t += kThreads)
 #pragma unroll
             for (int c = 0; c < kNv; ++c) out[c * variant_stride + t] = 0.f;
@@ -1014,7 +1018,7 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
     const int n_total = (n_blk + 3) & ~3;
     int n_plain = (vis_min + 1 - t_begin) / 32;
     n_plain = has_special ? 0 : (max(0, min(n_plain, n_blk)) & ~3);
-#define OBC_S2_ARGS smem, lds0, n, n_blk, t_begin, t_end, len - 1, vis_i, excl_i, kh, vh, kp, kdoff, wave, lane, wave_active, part, out, variant_stride
+#define OBC_S2_ARGS smem, lds0, n, n_blk, t_begin, t_end, len - 1, vis_i, excl_i, kh, vh, kp, kdoff, wave, lane, wave_active, part, out, variant_stride, accumulate
     int n = 0;
     for (; n < n_plain; n += 4) {
         sweep2_step<0, false, kVariant>(R, OBC_S2_ARGS); ++n;
@@ -1031,10 +1035,11 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
 #undef OBC_S2_ARGS
     __syncthreads();
     // The last tile's partial sums (second staging slot: n_total is a multiple of 4), then zeros for the padding.
-    sweep2_flush<kNv>(part + 4 * kNv * 64, out, variant_stride, t_begin + (n_total - 2) * 32, t_end, wave, lane);
-    for (int t = t_end + threadIdx.x; t < t_stop; t += kThreads)
+    sweep2_flush<kNv>(part + 4 * kNv * 64, out, variant_stride, t_begin + (n_total - 2) * 32, t_end, wave, lane, accumulate);
+    if (!accumulate)
+        for (int t = t_end + threadIdx.x; t < t_stop; t += kThreads)
 #pragma unroll
-        for (int c = 0; c < kNv; ++c) out[c * variant_stride + t] = 0.f;
+            for (int c = 0; c < kNv; ++c) out[c * variant_stride + t] = 0.f;
     if (has_special) {      // add the separately scored pairs, in row order, by one thread
         __syncthreads();
         if (threadIdx.x == 0) {
@@ -1053,12 +1058,13 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
 
 // scores[c][idx] = sum over chunks of planes[chunk][c][idx], in chunk order.
 __global__ __launch_bounds__(256) void mfma_sum_planes(const float *__restrict__ planes, int n_chunks,
-                                                       size_t chunk_stride, size_t total, float *__restrict__ scores) {
+                                                       size_t chunk_stride, size_t total, float *__restrict__ scores,
+                                                       int accumulate) {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
     float s = 0.f;
     for (int c = 0; c < n_chunks; ++c) s += planes[(size_t)c * chunk_stride + i];
-    scores[i] = s;
+    scores[i] = accumulate ? scores[i] + s : s;        // the planes hold 0 beyond the true length
 }
 
 template <int kVariant>
@@ -1074,11 +1080,13 @@ hipError_t launch_sweep2(const ScoreArgs &a, const ScoreWorkspace &ws, char *bas
     mfma_sweep2<kVariant><<<grid, dim3(kThreads), lds, stream>>>(
         (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens,
         ws.range_len, ws.m_pad, (const uint16_t *)(base + ws.out_bf16), (const float *)(base + ws.row_const),
-        (const float *)(base + ws.special), dst, plane_elems, chunk_stride);
+        (const float *)(base + ws.special), dst, plane_elems, chunk_stride,
+        ws.n_chunks == 1 ? a.accumulate : 0);
     e = hipGetLastError();
     if (e != hipSuccess || ws.n_chunks == 1) return e;
     const size_t total = plane_elems * nv;
-    mfma_sum_planes<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(dst, ws.n_chunks, chunk_stride, total, a.scores);
+    mfma_sum_planes<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(dst, ws.n_chunks, chunk_stride, total, a.scores,
+                                                                                 a.accumulate);
     return hipGetLastError();
 }
 

@@ -195,7 +195,7 @@ __global__ __launch_bounds__(kThreads) void plain_score(
     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v, int N, int W, int Hq, int Hkv,
     int ragged, SeqLens lens, int variant, const float *__restrict__ row_max, const float *__restrict__ row_sum,
     const float *__restrict__ out, const float *__restrict__ out_rest, const float *__restrict__ rest_frac,
-    const int32_t *__restrict__ top_token, float *__restrict__ scores, size_t variant_stride) {
+    const int32_t *__restrict__ top_token, float *__restrict__ scores, size_t variant_stride, int accumulate) {
     extern __shared__ float smem[];
     float *ks = smem;                          // [kTile][D+1]
     float *vs = ks + kTile * (D + 1);          // [kTile][D+1]
@@ -261,7 +261,16 @@ __global__ __launch_bounds__(kThreads) void plain_score(
                    (red[(2 * kTile + tok) * 3 + c] + red[(3 * kTile + tok) * 3 + c]);
         const size_t idx = (size_t)bg * N + p;
         const bool live = p < len;
-        if (variant == OBC_ALL) {
+        if (accumulate) {                       // running scores: add this call's increment, leave the padding alone
+            if (live) {
+                if (variant == OBC_ALL) {
+#pragma unroll
+                    for (int c = 0; c < 3; ++c) scores[c * variant_stride + idx] += s[c];
+                } else {
+                    scores[idx] += s[variant];
+                }
+            }
+        } else if (variant == OBC_ALL) {
 #pragma unroll
             for (int c = 0; c < 3; ++c) scores[c * variant_stride + idx] = live ? s[c] : 0.f;
         } else {
@@ -294,7 +303,7 @@ hipError_t run(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStre
     const dim3 grid((a.N + kTile - 1) / kTile, a.B * a.Hkv);
     plain_score<T, D><<<grid, dim3(kThreads), lds2, stream>>>(
         (const T *)a.q, (const T *)a.k, (const T *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, a.variant, row_max,
-        row_sum, out, out_rest, rest_frac, top_token, a.scores, (size_t)a.B * a.Hkv * a.N);
+        row_sum, out, out_rest, rest_frac, top_token, a.scores, (size_t)a.B * a.Hkv * a.N, a.accumulate);
     return hipGetLastError();
 }
 

@@ -177,3 +177,54 @@ def test_runtime_errors_surface():
     assert e.value.status == obc.OBC_EINVAL
     with pytest.raises(obc.ObcError):
         obc.obc_select(torch.zeros(1, 1, 8, device=dev), 9)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_decode_accumulation_matches_oracle(dtype):
+    """Prefill scores, then T decode steps (W = 1, cache one token longer each step) accumulated in place."""
+    wl = synth.Workload("decode_" + dtype, B=2, Hq=8, Hkv=2, d=128, N=700, W=16, dtype=dtype, budget=64, seed=31,
+                        sinks=2, outlier_channels=2)
+    x = synth.make_inputs(wl)
+    dev = to_device(x)
+    T, L0 = 24, [600, 333]                                # prefill lengths; the cache grows to L0 + T
+    tol = TOL[dtype]
+    g = torch.Generator().manual_seed(32)
+    qd = torch.randn(T, wl.B, wl.Hq, 1, wl.d, generator=g).to(x["q"].dtype)
+    ref = np.asarray(oracle.score(x["q"], x["k"], x["v"], seq_lens=L0))
+    run = obc.obc_score(dev["q"], dev["k"], dev["v"], "all", seq_lens=L0)
+    sentinel = 123.0
+    for b in range(wl.B):
+        run[:, b, :, L0[b] + T:] = sentinel               # positions no step reaches must stay untouched
+    for t in range(T):
+        lens_t = [L + t + 1 for L in L0]
+        ref += np.asarray(oracle.score(qd[t], x["k"], x["v"], seq_lens=lens_t))
+        obc.obc_score(qd[t].cuda(), dev["k"], dev["v"], "all", seq_lens=lens_t, scores=run, accumulate=True)
+    torch.cuda.synchronize()
+    final = [L + T for L in L0]
+    for vi, name in enumerate(synth.VARIANTS):
+        gpu = run[vi].cpu().numpy()
+        for b in range(wl.B):
+            assert np.all(gpu[b, :, final[b]:] == sentinel), name
+            gpu[b, :, final[b]:] = 0.0
+        err, where = score_error(gpu, ref[vi], wl.budget, final, tol)
+        assert err <= tol, "%s: err %.3g at %s" % (name, err, where)
+    # single-variant accumulation takes the same path as the all-variant one
+    one = obc.obc_score(dev["q"], dev["k"], dev["v"], "joint", seq_lens=L0)
+    obc.obc_score(qd[0].cuda(), dev["k"], dev["v"], "joint", seq_lens=[L + 1 for L in L0], scores=one, accumulate=True)
+    two = obc.obc_score(dev["q"], dev["k"], dev["v"], "joint", seq_lens=L0)
+    inc = obc.obc_score(qd[0].cuda(), dev["k"], dev["v"], "joint", seq_lens=[L + 1 for L in L0])
+    for b in range(wl.B):
+        n = L0[b] + 1
+        assert torch.equal(one[b, :, :n], two[b, :, :n] + inc[b, :, :n])
+
+
+def test_accumulate_onto_zeros_equals_plain_call_with_several_row_chunks():
+    """G*W = 448 window rows: four row chunks whose planes are summed by a second kernel; that path accumulates too."""
+    wl = CASES["s_bf16_qwen"]
+    dev = to_device(synth.make_inputs(wl))
+    plain = obc.obc_score(dev["q"], dev["k"], dev["v"], "all")
+    run = torch.zeros_like(plain)
+    obc.obc_score(dev["q"], dev["k"], dev["v"], "all", scores=run, accumulate=True)
+    assert torch.equal(run, plain)
+    obc.obc_score(dev["q"], dev["k"], dev["v"], "all", scores=run, accumulate=True)
+    assert torch.equal(run, plain + plain)

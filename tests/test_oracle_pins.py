@@ -425,3 +425,21 @@ def test_select_pooled_window_stays_inside_candidates_and_hand_case():
     np.testing.assert_array_equal(got[1, 0], [0, 1, 2])          # sums: p0..p4 = 1, p5 = 0
     with pytest.raises(ValueError):
         oracle.select_pooled(t, 3, pool=4)
+
+
+# ---- decoding-time accumulation (Section 4.2 closing remark; Eq. 9) ----
+
+def test_window_score_is_sum_of_single_row_steps_with_growing_cache():
+    """Eq. 9 sums independent per-row terms: a W-row causal window equals W decode steps (one query row each,
+    cache length = the row's position + 1) added up.  Pins the causal mask row by row and is what
+    obc_score_accumulate relies on."""
+    rng = np.random.default_rng(85)
+    B, Hq, Hkv, N, W, d = 2, 4, 2, 90, 6, 8
+    q = rng.standard_normal((B, Hq, W, d)); k = rng.standard_normal((B, Hkv, N, d)); v = rng.standard_normal((B, Hkv, N, d))
+    lens = [90, 41]
+    whole = np.asarray(oracle.score(q, k, v, seq_lens=lens))
+    acc = np.zeros_like(whole)
+    for r in range(W):
+        step_lens = [L - W + r + 1 for L in lens]
+        acc += np.asarray(oracle.score(q[:, :, r:r + 1, :], k, v, seq_lens=step_lens))
+    np.testing.assert_allclose(acc, whole, rtol=1e-12, atol=1e-300)
