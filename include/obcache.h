@@ -184,6 +184,18 @@ int obc_compact(const void *k, const void *v, const int32_t *keep_idx,
                 int B, int Hkv, int N, int budget, int d, int dtype, void *hip_stream);
 
 /*
+ * Running scores follow their tokens through an eviction (Section 4.2, closing remark, and
+ * Appendix C, decoding setup: scores accumulate over time and an eviction is made at every
+ * step, so a kept token keeps its accumulated score):
+ *   scores_out[b,g,j] = scores[b,g,keep_idx[b,g,j]]  for j < budget,   0 for budget <= j < N_out.
+ *   scores      [B, Hkv, N] fp32        keep_idx [B, Hkv, budget] int32 (as for obc_compact)
+ *   scores_out  [B, Hkv, N_out] fp32, N_out >= budget; must not overlap scores.
+ * The zero tail leaves room for the tokens still to come in a cache of N_out slots.
+ */
+int obc_compact_scores(const float *scores, const int32_t *keep_idx, float *scores_out,
+                       int B, int Hkv, int N, int budget, int N_out, void *hip_stream);
+
+/*
  * Measurement hook (not part of the method): reads `bytes` bytes (a multiple of 16, 16-byte
  * aligned, device) once with 128-bit loads and writes one folded word per thread to
  * `sink` (device, OBC_PROBE_BLOCKS * 256 uint32).  Timed with events around the call it

@@ -64,6 +64,8 @@ def load_library():
     lib.obc_compact.restype = c_int
     lib.obc_compact.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int,
                                 c_int, c_void_p]
+    lib.obc_compact_scores.restype = c_int
+    lib.obc_compact_scores.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p]
     lib.obc_probe_read_bandwidth.restype = c_int
     lib.obc_probe_read_bandwidth.argtypes = [c_void_p, c_size_t, c_void_p, c_void_p]
     _lib = lib
@@ -229,6 +231,26 @@ def obc_compact(k: torch.Tensor, v: torch.Tensor, keep_idx: torch.Tensor, k_out=
     if rc != OBC_OK:
         raise ObcError(rc, "obc_compact")
     return k_out, v_out
+
+
+def obc_compact_scores(scores: torch.Tensor, keep_idx: torch.Tensor, n_out: Optional[int] = None,
+                       scores_out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """scores [B,Hkv,N] fp32, keep_idx [B,Hkv,budget] -> [B,Hkv,n_out]: gathered scores, then zeros."""
+    _require_cuda(scores, keep_idx)
+    B, Hkv, N = scores.shape
+    budget = keep_idx.shape[-1]
+    if scores.dtype != torch.float32 or keep_idx.dtype != torch.int32 or tuple(keep_idx.shape[:2]) != (B, Hkv):
+        raise ValueError("scores must be [B,Hkv,N] float32 and keep_idx [B,Hkv,budget] int32")
+    n_out = budget if n_out is None else int(n_out)
+    if scores_out is None:
+        scores_out = torch.empty((B, Hkv, n_out), dtype=torch.float32, device=scores.device)
+    elif tuple(scores_out.shape) != (B, Hkv, n_out) or scores_out.dtype != torch.float32 or not scores_out.is_contiguous():
+        raise ValueError("scores_out must be a contiguous [B,Hkv,%d] float32 tensor" % n_out)
+    rc = load_library().obc_compact_scores(scores.data_ptr(), keep_idx.data_ptr(), scores_out.data_ptr(), B, Hkv, N,
+                                           budget, n_out, _stream_ptr(scores))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_compact_scores")
+    return scores_out
 
 
 OBC_PROBE_BLOCKS = 2048

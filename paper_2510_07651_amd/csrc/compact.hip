@@ -22,6 +22,24 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4 *__restrict__ k, 
     out[t] = in[src];
 }
 
+// Running scores follow their tokens through an eviction: out[bg, j] = in[bg, keep[bg, j]] for
+// j < budget, 0 for budget <= j < n_out (slots of tokens still to come).
+__global__ __launch_bounds__(256) void gather_scores(const float *__restrict__ in, const int32_t *__restrict__ keep_idx,
+                                                     float *__restrict__ out, int N, int budget, int n_out,
+                                                     size_t total) {
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total) return;
+    const size_t bg = t / n_out;
+    const int j = (int)(t % n_out);
+    float x = 0.f;
+    if (j < budget) {
+        int p = keep_idx[bg * budget + j];
+        p = p < 0 ? 0 : (p >= N ? N - 1 : p);
+        x = in[bg * N + p];
+    }
+    out[t] = x;
+}
+
 // Measurement hook: reads `n_vec` 16-byte words once with 128-bit loads and folds them
 // into one word per thread (so the loads cannot be dropped).  Its duration gives the box's
 // own streaming-read ceiling, the practical denominator next to the nominal HBM peak.
@@ -37,6 +55,14 @@ __global__ __launch_bounds__(256) void stream_read(const uint4 *__restrict__ src
 }
 
 }  // namespace
+
+hipError_t launch_gather_scores(const float *in, const int32_t *keep_idx, float *out, int BH, int N, int budget,
+                                 int n_out, hipStream_t stream) {
+    const size_t total = (size_t)BH * n_out;
+    gather_scores<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(in, keep_idx, out, N, budget, n_out,
+                                                                                   total);
+    return hipGetLastError();
+}
 
 hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int blocks, hipStream_t stream) {
     stream_read<<<dim3(blocks), dim3(256), 0, stream>>>((const uint4 *)src, bytes / 16, sink);

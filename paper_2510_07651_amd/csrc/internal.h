@@ -62,6 +62,8 @@ hipError_t launch_select(const float *scores, int budget, int32_t *keep_idx, int
                          const SeqLens &lens, int first, int tail, int radius, hipStream_t stream);
 hipError_t launch_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_out, void *v_out, int B,
                           int Hkv, int N, int budget, int row_bytes, hipStream_t stream);
+hipError_t launch_gather_scores(const float *in, const int32_t *keep_idx, float *out, int BH, int N, int budget,
+                                 int n_out, hipStream_t stream);
 hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int blocks, hipStream_t stream);
 
 __device__ __forceinline__ int seq_len_of(const SeqLens &lens, int ragged, int b, int N) {

@@ -193,6 +193,16 @@ int obc_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_o
     return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
 }
 
+int obc_compact_scores(const float *scores, const int32_t *keep_idx, float *scores_out, int B, int Hkv, int N,
+                       int budget, int N_out, void *hip_stream) {
+    if (!scores || !keep_idx || !scores_out) return OBC_EINVAL;
+    if (B < 1 || Hkv < 1 || N < 1 || budget < 1 || N_out < budget) return OBC_EINVAL;
+    if ((long long)B * Hkv * N_out > (1LL << 40)) return OBC_EUNSUPPORTED;
+    const hipError_t e = launch_gather_scores(scores, keep_idx, scores_out, B * Hkv, N, budget, N_out,
+                                              (hipStream_t)hip_stream);
+    return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
+}
+
 int obc_probe_read_bandwidth(const void *buf, size_t bytes, uint32_t *sink, void *hip_stream) {
     if (!buf || !sink || bytes < 16 || bytes % 16 != 0) return OBC_EINVAL;
     if (((uintptr_t)buf & 15) != 0) return OBC_EINVAL;

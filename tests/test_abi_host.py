@@ -94,6 +94,9 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     assert pl(fake, 4, 0, 0, 0, 0, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
     assert pl(fake, 4, 0, 0, 0, 17, fake, 1, 1, 16, None, None) == obc.OBC_EUNSUPPORTED
     assert pl(fake, 17, 0, 0, 0, 5, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
+    cs = lib.obc_compact_scores            # (scores, keep, out, B, Hkv, N, budget, N_out, stream)
+    assert cs(fake, None, fake, 1, 1, 16, 4, 8, None) == obc.OBC_EINVAL
+    assert cs(fake, fake, fake, 1, 1, 16, 4, 3, None) == obc.OBC_EINVAL               # N_out < budget
     probe = lib.obc_probe_read_bandwidth
     assert probe(None, 1024, fake, None) == obc.OBC_EINVAL
     assert probe(fake, 1000, fake, None) == obc.OBC_EINVAL                            # not a multiple of 16

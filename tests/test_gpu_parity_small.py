@@ -228,3 +228,54 @@ def test_accumulate_onto_zeros_equals_plain_call_with_several_row_chunks():
     assert torch.equal(run, plain)
     obc.obc_score(dev["q"], dev["k"], dev["v"], "all", scores=run, accumulate=True)
     assert torch.equal(run, plain + plain)
+
+
+def test_decode_eviction_loop_matches_oracle():
+    """The decoding setup of Appendix C in miniature: every step appends a token, accumulates its scores, and once the
+    cache is over budget evicts one token per head with sinks and a recent window protected.  The oracle runs the same
+    loop in fp64; eviction decisions are taken on the same fp32 running scores on both sides and must be identical."""
+    B, Hq, Hkv, d = 2, 8, 2, 128
+    sinks, recent, hh = 4, 24, 36
+    budget = sinks + recent + hh                                  # 64 cache slots after an eviction
+    cap = budget + 1
+    T = 150
+    g = torch.Generator().manual_seed(41)
+    qs = torch.randn(T, B, Hq, 1, d, generator=g).to(torch.bfloat16)
+    ks = torch.randn(T, B, Hkv, d, generator=g).to(torch.bfloat16); ks[:, :, :, :3] *= 6.0
+    vs = torch.randn(T, B, Hkv, d, generator=g).to(torch.bfloat16)
+    dev = torch.device("cuda")
+    k = torch.zeros(B, Hkv, cap, d, dtype=torch.bfloat16, device=dev); v = torch.zeros_like(k)
+    run = torch.zeros(B, Hkv, cap, dtype=torch.float32, device=dev)
+    k_ref = np.zeros((B, Hkv, cap, d), np.float64); v_ref = np.zeros_like(k_ref)
+    run_ref = np.zeros((B, Hkv, cap), np.float64)
+    length, evictions = 0, 0
+    for t in range(T):
+        k[:, :, length] = ks[t].to(dev); v[:, :, length] = vs[t].to(dev)
+        k_ref[:, :, length] = ks[t].double().numpy(); v_ref[:, :, length] = vs[t].double().numpy()
+        length += 1
+        lens = [length] * B
+        obc.obc_score(qs[t].to(dev), k, v, "joint", seq_lens=lens, scores=run, accumulate=True)
+        run_ref += np.asarray(oracle.score(qs[t].double().numpy(), k_ref, v_ref, seq_lens=lens))[2]
+        if length > budget:
+            keep = obc.obc_select_protected(run, hh, sinks, recent, 0, seq_lens=lens)
+            keep_np = keep.cpu().numpy()
+            np.testing.assert_array_equal(keep_np, oracle.select_protected(run.cpu().numpy(), hh, sinks, recent, 0, lens))
+            ko, vo = obc.obc_compact(k, v, keep)
+            new_run = obc.obc_compact_scores(run, keep, n_out=cap)
+            k = torch.zeros_like(k); v = torch.zeros_like(v)
+            k[:, :, :budget] = ko; v[:, :, :budget] = vo
+            run = new_run
+            idx = keep_np[..., None]
+            k_new = np.zeros_like(k_ref); v_new = np.zeros_like(v_ref); r_new = np.zeros_like(run_ref)
+            k_new[:, :, :budget] = np.take_along_axis(k_ref, idx, axis=2)
+            v_new[:, :, :budget] = np.take_along_axis(v_ref, idx, axis=2)
+            r_new[:, :, :budget] = np.take_along_axis(run_ref, keep_np, axis=2)
+            k_ref, v_ref, run_ref = k_new, v_new, r_new
+            length = budget
+            evictions += 1
+            np.testing.assert_array_equal(k.double().cpu().numpy(), k_ref)         # the caches stay identical
+            assert np.all(run.cpu().numpy()[:, :, budget:] == 0.0)
+        if t % 10 == 9 or t == T - 1:
+            err, where = score_error(run.cpu().numpy(), run_ref, min(hh, length), [length] * B, TOL["bf16"])
+            assert err <= TOL["bf16"], "step %d: err %.3g at %s" % (t, err, where)
+    assert evictions == T - budget
