@@ -54,7 +54,9 @@ typedef enum {
     OBC_VALUE = 0,  /* Eq. 4: sum_i A_ip^2 ||v_p||^2 */
     OBC_KEY = 1,    /* Eq. 5: sum_i A_ip^2 Z_ip^2 ||v_p - o_i||^2 */
     OBC_JOINT = 2,  /* Eq. 6: value + key + 2 sum_i A_ip^2 Z_ip (||v_p||^2 - v_p.o_i) */
-    OBC_ALL = 3     /* all three; scores is [3][B][Hkv][N] in the order value, key, joint */
+    OBC_ALL = 3,    /* all three; scores is [3][B][Hkv][N] in the order value, key, joint */
+    OBC_ATTN = 4,   /* Eq. 8 (Section 4.3): sum_i |A_ip|, the attention-only score the method generalises */
+    OBC_VATP = 5    /* Appendix C, "VATP": the value score with the l1 norm, sum_i |A_ip| ||v_p||_1 */
 } obc_variant_t;
 
 typedef enum {

@@ -13,5 +13,6 @@ from .binding import (  # noqa: F401
     select,
     select_pooled,
     select_protected,
+    vatp_score,
     window_attention,
 )

@@ -50,6 +50,8 @@ def _load():
         lib.obc_oracle_score.argtypes = [dp, dp, dp] + [c_int] * 6 + [ip, c_int, dp, dp, dp]
         lib.obc_oracle_attn_score.restype = c_int
         lib.obc_oracle_attn_score.argtypes = [dp, dp, dp] + [c_int] * 6 + [ip, dp]
+        lib.obc_oracle_vatp_score.restype = c_int
+        lib.obc_oracle_vatp_score.argtypes = lib.obc_oracle_attn_score.argtypes
         lib.obc_oracle_select.restype = c_int
         lib.obc_oracle_select.argtypes = [fp, c_int, c_int, c_int, c_int, ip, ip]
         lib.obc_oracle_select_protected.restype = c_int
@@ -132,6 +134,17 @@ def attn_score(q, k, v, seq_lens=None):
     s = np.empty((B, Hkv, N))
     rc = _load().obc_oracle_attn_score(_dptr(q), _dptr(k), _dptr(v), B, Hq, Hkv, N, W, d, lp, _dptr(s))
     _check(rc, "attn_score")
+    return s
+
+
+def vatp_score(q, k, v, seq_lens=None):
+    """sum_i |A_ip| * ||v_p||_1 per (b, KV head, token): the paper's reproduction of VATP."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    B, Hq, Hkv, N, W, d = _shapes(q, k, v)
+    keep, lp = _lens(seq_lens, B)
+    s = np.empty((B, Hkv, N))
+    rc = _load().obc_oracle_vatp_score(_dptr(q), _dptr(k), _dptr(v), B, Hq, Hkv, N, W, d, lp, _dptr(s))
+    _check(rc, "vatp_score")
     return s
 
 

@@ -252,6 +252,26 @@ int obc_oracle_attn_score(const double *q, const double *k, const double *v,
     return OBC_ORACLE_OK;
 }
 
+/*
+ * VATP score as the paper reproduces it (Appendix C, "VATP and CriticalKV": the value
+ * score with the l2 norm replaced by the l1 norm): S_p = sum_i |A_ip| * ||v_p||_1,
+ * summed over the window and the query heads of the group; v_p is the group's shared
+ * value row, so the norm factors out of the sums.
+ */
+int obc_oracle_vatp_score(const double *q, const double *k, const double *v,
+                          int B, int Hq, int Hkv, int N, int W, int d,
+                          const int32_t *seq_lens, double *s_vatp)
+{
+    int rc = obc_oracle_attn_score(q, k, v, B, Hq, Hkv, N, W, d, seq_lens, s_vatp);
+    if (rc) return rc;
+    for (size_t t = 0; t < (size_t)B * Hkv * N; ++t) {
+        double l1 = 0.0;
+        for (int j = 0; j < d; ++j) l1 += fabs(v[t * d + j]);
+        s_vatp[t] = s_vatp[t] == 0.0 ? 0.0 : s_vatp[t] * l1;   /* padded rows may hold NaN: never multiplied in */
+    }
+    return OBC_ORACLE_OK;
+}
+
 /* ---- selection (Section 3 "Cache Eviction"; Algorithm 2: topk -> sort) ---- */
 
 typedef struct { float s; int32_t p; } scored_t;

@@ -16,10 +16,11 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libobcache.so")
 
-OBC_VALUE, OBC_KEY, OBC_JOINT, OBC_ALL = 0, 1, 2, 3
+OBC_VALUE, OBC_KEY, OBC_JOINT, OBC_ALL, OBC_ATTN, OBC_VATP = 0, 1, 2, 3, 4, 5
 OBC_F32, OBC_BF16 = 0, 1
 OBC_OK, OBC_EINVAL, OBC_EUNSUPPORTED, OBC_EWORKSPACE, OBC_ELAUNCH = 0, -1, -2, -3, -4
-VARIANT_CODES = {"value": OBC_VALUE, "key": OBC_KEY, "joint": OBC_JOINT, "all": OBC_ALL}
+VARIANT_CODES = {"value": OBC_VALUE, "key": OBC_KEY, "joint": OBC_JOINT, "all": OBC_ALL, "attn": OBC_ATTN,
+                 "vatp": OBC_VATP}
 
 _lib = None
 

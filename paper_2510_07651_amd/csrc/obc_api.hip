@@ -12,7 +12,7 @@ static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 static int check_score_shape(int B, int N, int W, int Hq, int Hkv, int d, int dtype, int variant) {
     if (B < 1 || N < 1 || W < 1 || Hq < 1 || Hkv < 1 || d < 1) return OBC_EINVAL;
     if (Hq % Hkv != 0 || W > N) return OBC_EINVAL;
-    if (variant < OBC_VALUE || variant > OBC_ALL) return OBC_EINVAL;
+    if (variant < OBC_VALUE || variant > OBC_VATP) return OBC_EINVAL;
     if (dtype != OBC_F32 && dtype != OBC_BF16) return OBC_EUNSUPPORTED;
     if (d != 64 && d != 128) return OBC_EUNSUPPORTED;
     if (W > OBC_MAX_WINDOW || (Hq / Hkv) * W > OBC_MAX_GROUP_ROWS) return OBC_EUNSUPPORTED;

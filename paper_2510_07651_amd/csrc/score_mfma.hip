@@ -175,6 +175,13 @@ __device__ __forceinline__ f32x16 zero16() {
 
 union PiecePair { bf16x8 v; uint32_t u[4]; };
 
+// bf16 bits of -2 x for bf16 bits of x (exact: a power-of-two scaling).  The second sweep's
+// stationary o_i pieces are stored this way so that its cross-term accumulator holds
+// -2 v_p.o_i, the form the squared distances need.
+__device__ __forceinline__ uint16_t minus_twice_bf16(uint16_t bits) {
+    return (uint16_t)(__float_as_uint(-2.0f * __uint_as_float((uint32_t)bits << 16)) >> 16);
+}
+
 // Pins a value loaded from global memory as "consumed here", so that the wait for its load
 // is placed here (before the pipelined loops) and not inside them, where it would also
 // wait for the direct-to-LDS tile loads in flight.
@@ -531,8 +538,8 @@ __global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ pa
     __syncthreads();
     const size_t grow = ((size_t)b * Hq + (size_t)g * G) * W + row;
     out_f32[grow * kD + dd] = o;
-    out_bf16[crow * kD + dd] = ob;
-    out_bf16[lo_plane + crow * kD + dd] = olo;
+    out_bf16[crow * kD + dd] = minus_twice_bf16(ob);
+    out_bf16[lo_plane + crow * kD + dd] = minus_twice_bf16(olo);
     if (dd == 0) {
         row_max[grow] = m * 0.6931471805599453f;      // natural-log units
         row_sum[grow] = l;
@@ -749,8 +756,8 @@ __global__ __launch_bounds__(128) void mfma_rescue_combine(const uint16_t *__res
     __syncthreads();
     const size_t grow = ((size_t)b * Hq + (size_t)g * G) * W + row;
     out_f32[grow * kD + dd] = o;
-    out_bf16[crow * kD + dd] = ob;
-    out_bf16[lo_plane + crow * kD + dd] = olo;
+    out_bf16[crow * kD + dd] = minus_twice_bf16(ob);
+    out_bf16[lo_plane + crow * kD + dd] = minus_twice_bf16(olo);
     if (dd == 0) {
         const float a = 1.0f / ltot, a2 = a * a;
         row_sum[grow] = ltot;
@@ -794,6 +801,19 @@ __device__ __forceinline__ float sumsq8(const bf16x8 x, float acc) {
     return acc;
 }
 
+// Sum of the absolute values of the 8 bf16 values in a 16-byte operand piece: each pair is
+// dotted with (+-1, +-1) carrying the pair's own signs.
+__device__ __forceinline__ float sumabs8(const bf16x8 x, float acc) {
+    union { bf16x8 v; uint32_t u[4]; bf16x2 h[4]; } in, sg;
+    in.v = x;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        sg.u[e] = (in.u[e] & 0x80008000u) | 0x3f803f80u;
+        acc = __builtin_amdgcn_fdot2_f32_bf16(in.h[e], sg.h[e], acc, false);
+    }
+    return acc;
+}
+
 struct Sweep2Regs {
     bf16x8 q[8], ohi[8], olo[8];   // stationary A operands of this wave's row block
     float c_m2[16], c_oo[16];      // per accumulator register: 2 (max + log2 sum), ||o^||^2 of its row
@@ -828,6 +848,7 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
     constexpr bool kDoV = kVariant == OBC_VALUE || kVariant == OBC_ALL;
     constexpr bool kDoK = kVariant == OBC_KEY || kVariant == OBC_ALL;
     constexpr bool kDoJ = kVariant == OBC_JOINT || kVariant == OBC_ALL;
+    constexpr bool kDoA = kVariant == OBC_ATTN || kVariant == OBC_VATP;   // Eq. 8 and its l1-weighted form
     constexpr bool kNeedVO = kDoK || kDoJ;
     constexpr int kSlot = PH >> 1, kBlk = PH & 1;
     constexpr int kKBase = (kSlot ? kLdsK1 : kLdsK0) + kBlk * 32 * kRowBytes;
@@ -841,7 +862,8 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
         const int tn = t_begin + ((n >> 1) + 1) * kTileTok;           // first token of the tile to start now
         if (tn < t_end) {
             tile_load_async<kXor16>(kh, tn, last_row, lds0 + (PH == 0 ? kLdsK1 : kLdsK0), wave, lane, kdoff);
-            tile_load_async<kXor16>(vh, tn, last_row, lds0 + (PH == 0 ? kLdsV1 : kLdsV0), wave, lane, kdoff);
+            if (kVariant != OBC_ATTN)
+                tile_load_async<kXor16>(vh, tn, last_row, lds0 + (PH == 0 ? kLdsV1 : kLdsV0), wave, lane, kdoff);
         }
         if (n >= 2) sweep2_flush<kNv>(part + (kSlot ^ 1) * 4 * kNv * 64, out, variant_stride, t_begin + (n - 2) * 32, t_end, wave, lane, accumulate);
     }
@@ -858,8 +880,9 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
         }
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
+            if (kVariant == OBC_ATTN) break;                           // no use for V at all
             const bf16x8 vb = lds_read16(kp[kk] + kVBase);
-            vv = sumsq8(vb, vv);
+            vv = kVariant == OBC_VATP ? sumabs8(vb, vv) : sumsq8(vb, vv);
             if (kNeedVO) {
                 vo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.ohi[kk], vb, vo, 0, 0, 0);
                 vo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.olo[kk], vb, vo, 0, 0, 0);
@@ -867,43 +890,48 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
         }
         vv += other_half(vv);                                          // ||v_p||^2 of this lane's token
         // ---- vector ALUs ----
+        // vo holds -2 v_p.o^_i (the stationary pieces are stored pre-scaled by -2, an exact
+        // scaling), so with w = ||v_p - o^_i||^2 = (||v_p||^2 + ||o^_i||^2) + vo:
+        //   Eq. 5 term  A^2 Z^2 w
+        //   Eq. 6 term  A^2 ||(1+Z) v - Z o^||^2 = A^2 (||v||^2 + Z (2 (||v||^2 - v.o^) + Z w))
+        // Rounding can leave a term a hair below zero; the sums are clamped once at the end.
         const int tok = t_begin + n * 32 + (lane & 31);
+        const float vv2 = vv + vv;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            float a2 = __builtin_amdgcn_exp2f(fmaf(z[r], c2x2, -R.c_m2[r]));      // A_ip^2
+            // A_ip^2, or A_ip itself (half the exponent) for the attention-only scores
+            float a2 = kDoA ? __builtin_amdgcn_exp2f(fmaf(z[r], 0.5f * c2x2, -0.5f * R.c_m2[r]))
+                            : __builtin_amdgcn_exp2f(fmaf(z[r], c2x2, -R.c_m2[r]));
             if (kMasked) {
                 const int i = wave * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
                 if (tok > vis_i[i] || tok >= t_end || tok == excl_i[i]) a2 = 0.f; // hidden, padded, or scored separately
             }
-            const float zz = z[r] * kInvSqrtD;                                    // Z_ip
-            if (kDoV) acc_v += a2;
-            if (kDoK) {
-                const float nrm = fmaf(vo[r], -2.0f, vv + R.c_oo[r]);             // ||v_p - o^_i||^2
-                acc_k = fmaf(a2 * zz * zz, fmaxf(nrm, 0.f), acc_k);
-            }
-            if (kDoJ) {
-                // ||(1+Z) v - Z o^||^2 = (1+Z)^2 ||v||^2 - 2 Z (1+Z) v.o^ + Z^2 ||o^||^2
-                const float y = zz + 1.0f;
-                const float t1 = zz * vo[r];
-                const float t2 = fmaf(t1, -2.0f, y * vv);
-                const float t3 = fmaf(zz * R.c_oo[r], zz, y * t2);
-                acc_j = fmaf(a2, fmaxf(t3, 0.f), acc_j);
+            if (kDoV || kDoA) acc_v += a2;
+            if (kNeedVO) {
+                const float zz = z[r] * kInvSqrtD;                                // Z_ip
+                const float w = (vv + R.c_oo[r]) + vo[r];                         // ||v_p - o^_i||^2
+                if (kDoK) acc_k = fmaf(a2 * zz * zz, w, acc_k);
+                if (kDoJ) {
+                    const float h = fmaf(zz, w, vv2 + vo[r]);
+                    acc_j = fmaf(a2, fmaf(zz, h, vv), acc_j);
+                }
             }
         }
-        if (kDoV) { acc_v *= vv; acc_v += other_half(acc_v); }
-        if (kDoK) acc_k += other_half(acc_k);
-        if (kDoJ) acc_j += other_half(acc_j);
+        if (kDoV || kVariant == OBC_VATP) acc_v *= vv;                 // ||v_p||^2, or ||v_p||_1 for the l1 form
+        if (kDoV || kDoA) acc_v += other_half(acc_v);
+        if (kDoK) { acc_k += other_half(acc_k); acc_k = fmaxf(acc_k, 0.f); }
+        if (kDoJ) { acc_j += other_half(acc_j); acc_j = fmaxf(acc_j, 0.f); }
     }
     if (half == 0) {
         float *pw = part + ((kSlot * 4 + wave) * kNv) * 64 + kBlk * 32 + lane;
         int c = 0;
-        if (kDoV) pw[64 * c++] = acc_v;
+        if (kDoV || kDoA) pw[64 * c++] = acc_v;
         if (kDoK) pw[64 * c++] = acc_k;
         if (kDoJ) pw[64 * c++] = acc_j;
     }
 }
 
-// kVariant: OBC_VALUE / OBC_KEY / OBC_JOINT / OBC_ALL.  Grid: x = token range, y = chunk, z = (b, KV head).
+// kVariant: OBC_VALUE / OBC_KEY / OBC_JOINT / OBC_ALL / OBC_ATTN / OBC_VATP.  Grid: x = token range, y = chunk, z = (b, KV head).
 // With one chunk the scores go straight to `scores`; with several, each chunk writes its
 // own plane and mfma_sum_planes adds them in chunk order.
 template <int kVariant>
@@ -918,7 +946,7 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
                                                            size_t chunk_stride, int accumulate_flag) {
     const bool accumulate = accumulate_flag != 0;      // add to what `dst` holds; padded positions stay untouched
     constexpr int kNv = kVariant == OBC_ALL ? 3 : 1;
-    constexpr bool kNeedVO = kVariant != OBC_VALUE;
+    constexpr bool kNeedVO = kVariant == OBC_KEY || kVariant == OBC_JOINT || kVariant == OBC_ALL;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     float *vis_s = (float *)(smem + kLdsTiles);                // [128] last visible key of each row of the chunk
     float *excl_s = vis_s + 128;                               // [128] key of the row that is scored separately, or -1
@@ -956,7 +984,7 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
     uint32_t kdoff[4];
     tile_lane_offsets<kXor16>(kdoff, wave, lane);
     tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane, kdoff);
-    tile_load_async<kXor16>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane, kdoff);
+    if (kVariant != OBC_ATTN) tile_load_async<kXor16>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane, kdoff);
 
     int koff[8];
 #pragma unroll
@@ -1128,7 +1156,7 @@ void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWo
 }
 
 hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStream_t stream) {
-    const bool need_o = a.variant != OBC_VALUE;
+    const bool need_o = a.variant == OBC_KEY || a.variant == OBC_JOINT || a.variant == OBC_ALL;
     float *part_ml = (float *)(base + ws.part_ml), *part_o = (float *)(base + ws.part_o);
     int32_t *dom_rows = (int32_t *)(base + ws.dom_rows);
     int32_t *dom_count = dom_rows + (size_t)a.B * a.Hkv * ws.m_pad;
@@ -1168,6 +1196,8 @@ hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char 
         case OBC_VALUE: return launch_sweep2<OBC_VALUE>(a, ws, base, stream);
         case OBC_KEY: return launch_sweep2<OBC_KEY>(a, ws, base, stream);
         case OBC_JOINT: return launch_sweep2<OBC_JOINT>(a, ws, base, stream);
+        case OBC_ATTN: return launch_sweep2<OBC_ATTN>(a, ws, base, stream);
+        case OBC_VATP: return launch_sweep2<OBC_VATP>(a, ws, base, stream);
         default: return launch_sweep2<OBC_ALL>(a, ws, base, stream);
     }
 }

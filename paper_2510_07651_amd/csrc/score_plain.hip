@@ -210,6 +210,7 @@ __global__ __launch_bounds__(kThreads) void plain_score(
     const int rq = __builtin_amdgcn_readfirstlane(threadIdx.x / kTile);
     const int p = t0 + tok;
 
+    const bool attn_like = variant == OBC_ATTN || variant == OBC_VATP;   // these use the first accumulator
     float acc_v = 0.f, acc_k = 0.f, acc_j = 0.f;
     if (t0 < len) {                            // uniform per block
         stage_rows<T, D>(k + (size_t)bg * N * D, t0, len, ks);
@@ -217,8 +218,8 @@ __global__ __launch_bounds__(kThreads) void plain_score(
         __syncthreads();
         const float *kp = ks + tok * (D + 1), *vp = vs + tok * (D + 1);
         float *qw = qs + rq * D;               // private to this wave: no block barrier needed around it
-        float vv = 0.f;
-        for (int j = 0; j < D; ++j) vv = fmaf(vp[j], vp[j], vv);
+        float vv = 0.f, l1 = 0.f;
+        for (int j = 0; j < D; ++j) { vv = fmaf(vp[j], vp[j], vv); l1 += fabsf(vp[j]); }
         for (int hh = 0; hh < G; ++hh) {
             const int h = g * G + hh;
             for (int r = rq; r < W; r += 4) {
@@ -232,6 +233,10 @@ __global__ __launch_bounds__(kThreads) void plain_score(
                     const float z = scaled_logit<D>(qw, kp);
                     const bool is_top = p == ptop;
                     const float a = is_top ? inv_l : expf(z - m) * inv_l;
+                    if (attn_like) {                       // Eq. 8: only the weight itself is summed
+                        acc_v += a;
+                        continue;
+                    }
                     const float a2 = a * a;
                     const float f = is_top ? frac : 1.0f;
                     float dk = 0.f, dj = 0.f;
@@ -248,6 +253,7 @@ __global__ __launch_bounds__(kThreads) void plain_score(
                 }
             }
         }
+        if (variant == OBC_VATP) acc_v *= l1;
     }
     red[(rq * kTile + tok) * 3 + 0] = acc_v;
     red[(rq * kTile + tok) * 3 + 1] = acc_k;
@@ -267,14 +273,14 @@ __global__ __launch_bounds__(kThreads) void plain_score(
 #pragma unroll
                     for (int c = 0; c < 3; ++c) scores[c * variant_stride + idx] += s[c];
                 } else {
-                    scores[idx] += s[variant];
+                    scores[idx] += s[attn_like ? 0 : variant];
                 }
             }
         } else if (variant == OBC_ALL) {
 #pragma unroll
             for (int c = 0; c < 3; ++c) scores[c * variant_stride + idx] = live ? s[c] : 0.f;
         } else {
-            scores[idx] = live ? s[variant] : 0.f;
+            scores[idx] = live ? s[attn_like ? 0 : variant] : 0.f;
         }
     }
 }

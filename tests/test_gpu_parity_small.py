@@ -279,3 +279,24 @@ def test_decode_eviction_loop_matches_oracle():
             err, where = score_error(run.cpu().numpy(), run_ref, min(hh, length), [length] * B, TOL["bf16"])
             assert err <= TOL["bf16"], "step %d: err %.3g at %s" % (t, err, where)
     assert evictions == T - budget
+
+
+@pytest.mark.parametrize("name", ["s_fp32_gqa_ragged", "s_bf16_llama", "s_bf16_ragged", "s_bf16_qwen", "s_bf16_w1",
+                                  "s_bf16_strong_sink", "s_bf16_d64", "s_bf16_max_batch", "c1_single_head_fp32"])
+def test_attention_only_and_vatp_scores_match_oracle(name):
+    """Eq. 8 (sum of attention weights) and the l1-weighted form the paper reproduces VATP with."""
+    wl = CASES[name]
+    x = synth.make_inputs(wl)
+    dev = to_device(x)
+    lens = x["seq_lens"]
+    tol = TOL[wl.dtype]
+    for variant, ref in (("attn", oracle.attn_score(x["q"], x["k"], x["v"], seq_lens=lens)),
+                         ("vatp", oracle.vatp_score(x["q"], x["k"], x["v"], seq_lens=lens))):
+        gpu = obc.obc_score(dev["q"], dev["k"], dev["v"], variant, seq_lens=lens)
+        assert gpu.shape == (wl.B, wl.Hkv, wl.N)
+        g = gpu.cpu().numpy()
+        assert np.isfinite(g).all() and (g >= 0).all()
+        err, where = score_error(g, ref, wl.budget, lens, tol)
+        assert err <= tol, "%s %s: err %.3g at %s" % (name, variant, err, where)
+        keep = obc.obc_select(gpu, wl.budget, seq_lens=lens).cpu().numpy()
+        np.testing.assert_array_equal(keep, oracle.select(g, wl.budget, lens))

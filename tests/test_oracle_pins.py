@@ -443,3 +443,50 @@ def test_window_score_is_sum_of_single_row_steps_with_growing_cache():
         step_lens = [L - W + r + 1 for L in lens]
         acc += np.asarray(oracle.score(q[:, :, r:r + 1, :], k, v, seq_lens=step_lens))
     np.testing.assert_allclose(acc, whole, rtol=1e-12, atol=1e-300)
+
+
+# ---- attention-only score (Eq. 8) and its l1-weighted form (Appendix C, VATP paragraph) ----
+
+def test_attention_score_is_the_l11_change_when_a_column_of_A_is_zeroed():
+    """Eq. 8 by brute force: zero column p of the window rows of A (library softmax) and take the (1,1)-norm
+    of the change."""
+    g = torch.Generator().manual_seed(86)
+    N, W, d = 40, 5, 8
+    q = torch.randn(1, 1, W, d, generator=g, dtype=torch.float64)
+    k = torch.randn(1, 1, N, d, generator=g, dtype=torch.float64)
+    v = torch.randn(1, 1, N, d, generator=g, dtype=torch.float64)
+    Z = (q[0, 0] @ k[0, 0].T) / d ** 0.5
+    vis = torch.arange(N)[None, :] <= (N - W + torch.arange(W))[:, None]
+    A = torch.softmax(Z.masked_fill(~vis, float("-inf")), dim=-1)
+    want = np.empty(N)
+    for p in range(N):
+        Ap = A.clone(); Ap[:, p] = 0.0
+        want[p] = float((Ap - A).abs().sum())
+    np.testing.assert_allclose(oracle.attn_score(q.numpy(), k.numpy(), v.numpy())[0, 0], want, rtol=1e-12)
+
+
+def test_vatp_is_attention_score_times_l1_norm_and_ties_to_the_value_score():
+    rng = np.random.default_rng(87)
+    B, Hq, Hkv, N, W, d = 2, 4, 2, 60, 3, 16
+    q = rng.standard_normal((B, Hq, W, d)); k = rng.standard_normal((B, Hkv, N, d)); v = rng.standard_normal((B, Hkv, N, d))
+    lens = [60, 33]
+    sa = oracle.attn_score(q, k, v, seq_lens=lens)
+    sp = oracle.vatp_score(q, k, v, seq_lens=lens)
+    l1 = np.linalg.norm(v, ord=1, axis=-1)                         # library norm
+    np.testing.assert_allclose(sp, sa * l1, rtol=1e-13)
+    assert np.all(sp[1, :, 33:] == 0.0)
+    # scaling one value row scales only that token's score, by |alpha| (A does not depend on V)
+    v2 = v.copy(); v2[0, 1, 7] *= -2.5
+    sp2 = oracle.vatp_score(q, k, v2, seq_lens=lens)
+    np.testing.assert_allclose(sp2[0, 1, 7], 2.5 * sp[0, 1, 7], rtol=1e-13)
+    sp2[0, 1, 7] = sp[0, 1, 7]
+    np.testing.assert_array_equal(sp2, sp)
+    # one query head, one row, values in {-1, 0, 1}: ||v||_1 == ||v||_2^2 =: n, so VATP^2 == S^value * n
+    q1 = rng.standard_normal((1, 1, 1, d)); k1 = rng.standard_normal((1, 1, N, d))
+    v1 = rng.integers(-1, 2, (1, 1, N, d)).astype(np.float64)
+    n = np.abs(v1).sum(-1)
+    sv = oracle.score(q1, k1, v1)[0]
+    np.testing.assert_allclose(oracle.vatp_score(q1, k1, v1) ** 2, sv * n, rtol=1e-12)
+    # padded rows may hold NaN
+    v3 = v.copy(); v3[1, :, 33:] = np.nan; k3 = k.copy(); k3[1, :, 33:] = np.nan
+    np.testing.assert_array_equal(oracle.vatp_score(q, k3, v3, seq_lens=lens), sp)
