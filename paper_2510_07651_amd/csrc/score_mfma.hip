@@ -13,14 +13,17 @@
 //            terms O V^T on the matrix cores, with tokens on the lane axis of the
 //            accumulators so that the sum over window rows and query heads (Eq. 9,
 //            Appendix A.5) runs down registers; A^2 = exp2(2 log2e Z - 2 log2(max-shifted
-//            sum)) and the three scores are formed in fp32.
+//            sum)) and the three scores are formed in fp32.  The attention-only score
+//            of Eq. 8 and its l1-weighted form need Z only and skip the cross terms.
 //
-// Both sweeps walk their tokens in blocks of 32 with a software pipeline: while the vector
-// ALUs turn block n's accumulators into softmax weights (sweep 1) or scores (sweep 2), the
-// matrix cores already work on block n+1's contractions (and, in sweep 1, on block n-1's
-// P V product).  The streams of one step are independent, so they sit in one basic block
-// and the instruction scheduler interleaves them.  K/V tiles of 64 tokens travel
-// HBM -> LDS with direct-to-LDS loads, two steps ahead of their use.
+// Both sweeps walk their tokens in blocks of 32.  Sweep 1 is software-pipelined inside a
+// wave: while the vector ALUs turn block n's accumulators into softmax weights, the matrix
+// cores already work on block n+1's K Q^T and on block n-1's P V product; the streams of
+// one step are independent, sit in one basic block, and the instruction scheduler
+// interleaves them.  Sweep 2 runs a block's matrix phase and vector phase back to back and
+// leaves the overlap to the second wave on the SIMD (its stationary operands and row
+// constants leave no registers for a second set of accumulators).  K/V tiles of 64 tokens
+// travel HBM -> LDS with direct-to-LDS loads, two steps ahead of their use.
 //
 // Precision.  The matrix cores take bf16 operands, and rows whose attention is
 // concentrated on a few keys are sensitive to that rounding (the scores of those keys
