@@ -129,16 +129,28 @@ int obc_score_stages(const void *q, const void *k, const void *v,
                      void *workspace, size_t workspace_bytes, void *hip_stream, int stage_mask);
 
 /*
+ * Optional workspace of the three selection calls below.  Heads longer than 32768 tokens
+ * do not fit one block's registers; given *bytes_out bytes of 256-byte aligned device
+ * scratch their selection is cut into slices of 8192 tokens that run on separate blocks.
+ * *bytes_out is 0 for shapes that do not profit.  The results do not depend on whether the
+ * workspace is given.
+ */
+int obc_select_workspace_bytes(int B, int Hkv, int N, size_t *bytes_out);
+
+/*
  * Top-`budget` selection per (b, KV head) (Section 3 "Cache Eviction";
  * Algorithm 2).
  *   scores    [B, Hkv, N] fp32
  *   keep_idx  [B, Hkv, budget] int32, ascending token indices of the `budget`
  *             highest scores among p < len_b; equal scores are won by the lower
  *             index; -0.0 equals +0.0; NaN ranks below every number.
- * Requires 1 <= budget <= len_b for every b.  Needs no workspace.
+ *   workspace NULL, or obc_select_workspace_bytes(...) bytes of scratch (a smaller one is
+ *             ignored; a misaligned one is OBC_EWORKSPACE).
+ * Requires 1 <= budget <= len_b for every b.
  */
 int obc_select(const float *scores, int budget, int32_t *keep_idx,
-               int B, int Hkv, int N, const int32_t *seq_lens_host, void *hip_stream);
+               int B, int Hkv, int N, const int32_t *seq_lens_host,
+               void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Selection with protected regions (Appendix E, Algorithm 2: only positions below
@@ -155,7 +167,7 @@ int obc_select(const float *scores, int budget, int32_t *keep_idx,
  */
 int obc_select_protected(const float *scores, int num_hh, int num_sinks, int num_recent, int num_coming,
                          int32_t *keep_idx, int B, int Hkv, int N, const int32_t *seq_lens_host,
-                         void *hip_stream);
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Pooled selection (Appendix C, "SnapKV": the scores are smoothed by a one-dimensional
@@ -170,7 +182,7 @@ int obc_select_protected(const float *scores, int num_hh, int num_sinks, int num
 #define OBC_MAX_POOL 15
 int obc_select_pooled(const float *scores, int num_hh, int num_sinks, int num_recent, int num_coming, int pool,
                       int32_t *keep_idx, int B, int Hkv, int N, const int32_t *seq_lens_host,
-                      void *hip_stream);
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Compaction (Algorithm 2's gather; with indices from obc_select_protected the recent rows come along):

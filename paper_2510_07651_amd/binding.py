@@ -55,13 +55,15 @@ def load_library():
     lib.obc_score_stages.restype = c_int
     lib.obc_score_stages.argtypes = lib.obc_score.argtypes + [c_int]
     lib.obc_select.restype = c_int
-    lib.obc_select.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int, i32p, c_void_p]
+    lib.obc_select.argtypes = [c_void_p, c_int, c_void_p, c_int, c_int, c_int, i32p, c_void_p, c_size_t, c_void_p]
+    lib.obc_select_workspace_bytes.restype = c_int
+    lib.obc_select_workspace_bytes.argtypes = [c_int, c_int, c_int, ctypes.POINTER(c_size_t)]
     lib.obc_select_protected.restype = c_int
     lib.obc_select_protected.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_void_p, c_int, c_int, c_int, i32p,
-                                         c_void_p]
+                                         c_void_p, c_size_t, c_void_p]
     lib.obc_select_pooled.restype = c_int
     lib.obc_select_pooled.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_int, c_int, c_int, i32p,
-                                      c_void_p]
+                                      c_void_p, c_size_t, c_void_p]
     lib.obc_compact.restype = c_int
     lib.obc_compact.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int,
                                 c_int, c_void_p]
@@ -158,8 +160,31 @@ def obc_score(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, variant="joint"
     return scores
 
 
+def obc_select_workspace_bytes(B: int, Hkv: int, N: int) -> int:
+    out = ctypes.c_size_t(0)
+    rc = load_library().obc_select_workspace_bytes(B, Hkv, N, ctypes.byref(out))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_select_workspace_bytes")
+    return int(out.value)
+
+
+def _select_ws(scores: torch.Tensor, workspace):
+    """(pointer, bytes) of the optional selection scratch; allocates it when the shape profits and none was given.
+    workspace=False asks for the one-block-per-head path."""
+    if workspace is False:
+        return None, 0
+    B, Hkv, N = scores.shape
+    if workspace is None:
+        need = obc_select_workspace_bytes(B, Hkv, N)
+        if need == 0:
+            return None, 0
+        workspace = torch.empty(need, dtype=torch.uint8, device=scores.device)   # freed stream-ordered by torch
+    _require_cuda(workspace)
+    return workspace.data_ptr(), workspace.numel()
+
+
 def obc_select(scores: torch.Tensor, budget: int, seq_lens=None,
-               keep_idx: Optional[torch.Tensor] = None) -> torch.Tensor:
+               keep_idx: Optional[torch.Tensor] = None, workspace=None) -> torch.Tensor:
     """scores [B,Hkv,N] fp32 -> keep_idx [B,Hkv,budget] int32 ascending."""
     _require_cuda(scores)
     if scores.dtype != torch.float32 or scores.dim() != 3:
@@ -169,15 +194,17 @@ def obc_select(scores: torch.Tensor, budget: int, seq_lens=None,
         keep_idx = torch.empty((B, Hkv, max(int(budget), 0)), dtype=torch.int32, device=scores.device)
     elif keep_idx.dtype != torch.int32 or tuple(keep_idx.shape) != (B, Hkv, int(budget)) or not keep_idx.is_contiguous():
         raise ValueError("keep_idx must be a contiguous [B,Hkv,%d] int32 tensor" % int(budget))
+    ws_ptr, ws_bytes = _select_ws(scores, workspace)
     rc = load_library().obc_select(scores.data_ptr(), int(budget), keep_idx.data_ptr(), B, Hkv, N,
-                                   _lens_arg(seq_lens, B), _stream_ptr(scores))
+                                   _lens_arg(seq_lens, B), ws_ptr, ws_bytes, _stream_ptr(scores))
     if rc != OBC_OK:
         raise ObcError(rc, "obc_select")
     return keep_idx
 
 
 def obc_select_protected(scores: torch.Tensor, num_hh: int, num_sinks: int = 0, num_recent: int = 0,
-                         num_coming: int = 0, seq_lens=None, keep_idx: Optional[torch.Tensor] = None) -> torch.Tensor:
+                         num_coming: int = 0, seq_lens=None, keep_idx: Optional[torch.Tensor] = None,
+                         workspace=None) -> torch.Tensor:
     """scores [B,Hkv,N] fp32 -> keep_idx [B,Hkv,num_sinks+num_hh+num_recent-num_coming] int32 ascending."""
     _require_cuda(scores)
     if scores.dtype != torch.float32 or scores.dim() != 3:
@@ -188,16 +215,18 @@ def obc_select_protected(scores: torch.Tensor, num_hh: int, num_sinks: int = 0, 
         keep_idx = torch.empty((B, Hkv, max(total, 0)), dtype=torch.int32, device=scores.device)
     elif keep_idx.dtype != torch.int32 or tuple(keep_idx.shape) != (B, Hkv, total) or not keep_idx.is_contiguous():
         raise ValueError("keep_idx must be a contiguous [B,Hkv,%d] int32 tensor" % total)
+    ws_ptr, ws_bytes = _select_ws(scores, workspace)
     rc = load_library().obc_select_protected(scores.data_ptr(), int(num_hh), int(num_sinks), int(num_recent),
                                              int(num_coming), keep_idx.data_ptr(), B, Hkv, N,
-                                             _lens_arg(seq_lens, B), _stream_ptr(scores))
+                                             _lens_arg(seq_lens, B), ws_ptr, ws_bytes, _stream_ptr(scores))
     if rc != OBC_OK:
         raise ObcError(rc, "obc_select_protected")
     return keep_idx
 
 
 def obc_select_pooled(scores: torch.Tensor, num_hh: int, pool: int = 5, num_sinks: int = 0, num_recent: int = 0,
-                      num_coming: int = 0, seq_lens=None, keep_idx: Optional[torch.Tensor] = None) -> torch.Tensor:
+                      num_coming: int = 0, seq_lens=None, keep_idx: Optional[torch.Tensor] = None,
+                      workspace=None) -> torch.Tensor:
     """Like obc_select_protected, competitors ranked by their centred window sum of `pool` scores."""
     _require_cuda(scores)
     if scores.dtype != torch.float32 or scores.dim() != 3:
@@ -208,9 +237,10 @@ def obc_select_pooled(scores: torch.Tensor, num_hh: int, pool: int = 5, num_sink
         keep_idx = torch.empty((B, Hkv, max(total, 0)), dtype=torch.int32, device=scores.device)
     elif keep_idx.dtype != torch.int32 or tuple(keep_idx.shape) != (B, Hkv, total) or not keep_idx.is_contiguous():
         raise ValueError("keep_idx must be a contiguous [B,Hkv,%d] int32 tensor" % total)
+    ws_ptr, ws_bytes = _select_ws(scores, workspace)
     rc = load_library().obc_select_pooled(scores.data_ptr(), int(num_hh), int(num_sinks), int(num_recent),
                                           int(num_coming), int(pool), keep_idx.data_ptr(), B, Hkv, N,
-                                          _lens_arg(seq_lens, B), _stream_ptr(scores))
+                                          _lens_arg(seq_lens, B), ws_ptr, ws_bytes, _stream_ptr(scores))
     if rc != OBC_OK:
         raise ObcError(rc, "obc_select_pooled")
     return keep_idx

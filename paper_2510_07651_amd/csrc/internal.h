@@ -59,7 +59,10 @@ void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWo
 hipError_t launch_score_plain(const ScoreArgs &a, const ScoreWorkspace &ws, char *ws_base, hipStream_t stream);
 hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char *ws_base, hipStream_t stream);
 hipError_t launch_select(const float *scores, int budget, int32_t *keep_idx, int B, int Hkv, int N, int ragged,
-                         const SeqLens &lens, int first, int tail, int radius, hipStream_t stream);
+                         const SeqLens &lens, int first, int tail, int radius, void *workspace,
+                         size_t workspace_bytes, hipStream_t stream);
+size_t select_workspace_bytes(int B, int Hkv, int N);
+bool select_prefers_slices(int B, int Hkv, int N);
 hipError_t launch_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_out, void *v_out, int B,
                           int Hkv, int N, int budget, int row_bytes, hipStream_t stream);
 hipError_t launch_gather_scores(const float *in, const int32_t *keep_idx, float *out, int BH, int N, int budget,

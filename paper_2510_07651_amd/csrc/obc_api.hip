@@ -139,28 +139,23 @@ static int score_impl(const void *q, const void *k, const void *v, int N, int W,
     return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
 }
 
-int obc_select(const float *scores, int budget, int32_t *keep_idx, int B, int Hkv, int N,
-               const int32_t *seq_lens_host, void *hip_stream) {
-    if (!scores || !keep_idx) return OBC_EINVAL;
-    if (B < 1 || Hkv < 1 || N < 1 || budget < 1 || budget > N) return OBC_EINVAL;
+int obc_select_workspace_bytes(int B, int Hkv, int N, size_t *bytes_out) {
+    if (!bytes_out || B < 1 || Hkv < 1 || N < 1) return OBC_EINVAL;
     if ((long long)B * Hkv > 0x7fffffffLL / 2 || (long long)N > (1LL << 30)) return OBC_EUNSUPPORTED;
-    int ragged = 0;
-    SeqLens lens;
-    std::memset(&lens, 0, sizeof(lens));
-    const int rc = fill_lens(seq_lens_host, B, N, budget, &ragged, &lens);
-    if (rc != OBC_OK) return rc;
-    const hipError_t e = launch_select(scores, budget, keep_idx, B, Hkv, N, ragged, lens, 0, 0, 0, (hipStream_t)hip_stream);
-    return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
+    *bytes_out = select_prefers_slices(B, Hkv, N) ? select_workspace_bytes(B, Hkv, N) : 0;
+    return OBC_OK;
 }
 
 int obc_select_pooled(const float *scores, int num_hh, int num_sinks, int num_recent, int num_coming, int pool,
-                      int32_t *keep_idx, int B, int Hkv, int N, const int32_t *seq_lens_host, void *hip_stream) {
+                      int32_t *keep_idx, int B, int Hkv, int N, const int32_t *seq_lens_host, void *workspace,
+                      size_t workspace_bytes, void *hip_stream) {
     if (!scores || !keep_idx) return OBC_EINVAL;
     if (B < 1 || Hkv < 1 || N < 1) return OBC_EINVAL;
     if (num_hh < 0 || num_sinks < 0 || num_coming < 0 || num_recent < num_coming) return OBC_EINVAL;
     if (pool < 1 || pool % 2 == 0) return OBC_EINVAL;
     if (pool > OBC_MAX_POOL) return OBC_EUNSUPPORTED;
     if ((long long)B * Hkv > 0x7fffffffLL / 2 || (long long)N > (1LL << 30)) return OBC_EUNSUPPORTED;
+    if (workspace && ((uintptr_t)workspace & 255) != 0) return OBC_EWORKSPACE;
     const long long tail = (long long)num_recent - num_coming;
     const long long budget = (long long)num_sinks + num_hh + tail;     // every sequence must hold this many tokens
     if (budget < 1 || budget > N) return OBC_EINVAL;
@@ -170,14 +165,22 @@ int obc_select_pooled(const float *scores, int num_hh, int num_sinks, int num_re
     const int rc = fill_lens(seq_lens_host, B, N, (int)budget, &ragged, &lens);
     if (rc != OBC_OK) return rc;
     const hipError_t e = launch_select(scores, (int)budget, keep_idx, B, Hkv, N, ragged, lens, num_sinks, (int)tail,
-                                       (pool - 1) / 2, (hipStream_t)hip_stream);
+                                       (pool - 1) / 2, workspace, workspace_bytes, (hipStream_t)hip_stream);
     return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
 }
 
 int obc_select_protected(const float *scores, int num_hh, int num_sinks, int num_recent, int num_coming,
-                         int32_t *keep_idx, int B, int Hkv, int N, const int32_t *seq_lens_host, void *hip_stream) {
+                         int32_t *keep_idx, int B, int Hkv, int N, const int32_t *seq_lens_host, void *workspace,
+                         size_t workspace_bytes, void *hip_stream) {
     return obc_select_pooled(scores, num_hh, num_sinks, num_recent, num_coming, 1, keep_idx, B, Hkv, N, seq_lens_host,
-                             hip_stream);
+                             workspace, workspace_bytes, hip_stream);
+}
+
+int obc_select(const float *scores, int budget, int32_t *keep_idx, int B, int Hkv, int N,
+               const int32_t *seq_lens_host, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (budget < 1) return OBC_EINVAL;
+    return obc_select_pooled(scores, budget, 0, 0, 0, 1, keep_idx, B, Hkv, N, seq_lens_host, workspace,
+                             workspace_bytes, hip_stream);
 }
 
 int obc_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_out, void *v_out, int B, int Hkv,

@@ -571,7 +571,31 @@ __global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ pa
 // The (row, top key) pair is scored from these in fp32 (`special`), the second sweep skips
 // that pair and adds the stored values, and uses the refreshed o_i for all other keys.
 
-// Grid: x = sequence split, y = 128-row chunk of the dominant list, z = (b, KV head).
+// How a KV head's rescue work is cut up, as a function of the length of its dominant list.
+struct RescueLayout {
+    int list_chunks;   // 128-row chunks the list needs
+    int fine;          // sub-ranges every sequence split is cut into (spare chunk indices of the grid)
+    int sub_len;       // tokens per sub-range, a multiple of the tile
+    int list_rows;     // list positions stored per sub-range: min(list_chunks * 128, m_pad)
+};
+__device__ __forceinline__ RescueLayout rescue_layout(int count, int m_pad, int split_len) {
+    RescueLayout lay;
+    lay.list_chunks = (count + 127) / 128;
+    lay.fine = max(1, (m_pad / 128) / lay.list_chunks);
+    lay.sub_len = ((split_len + lay.fine - 1) / lay.fine + kTileTok - 1) / kTileTok * kTileTok;
+    lay.list_rows = min(lay.list_chunks * 128, m_pad);
+    return lay;
+}
+// Row of the partial-result arrays for (sub-split, list position): the head's share of the
+// arrays, n_splits * m_pad rows, is re-cut as [n_splits * fine][list_rows]; it fits because
+// fine * list_rows <= m_pad (fine > 1 only when fine * list_chunks * 128 <= m_pad).
+__device__ __forceinline__ size_t rescue_partial_row(const RescueLayout &lay, int bg, int n_splits, int m_pad,
+                                                     int sub_split, int slot) {
+    return (size_t)bg * n_splits * m_pad + (size_t)sub_split * lay.list_rows + slot;
+}
+
+// Grid: x = sequence split, y = 128-row chunk of the dominant list (or token sub-range, see
+// RescueLayout), z = (b, KV head).
 __global__ __launch_bounds__(kThreads, 2) void mfma_rescue_sweep(const uint16_t *__restrict__ q,
                                                                  const uint16_t *__restrict__ k,
                                                                  const uint16_t *__restrict__ v, int N, int W, int Hq,
@@ -583,14 +607,21 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_rescue_sweep(const uint16_t 
                                                                  float *__restrict__ part_ml,
                                                                  float *__restrict__ part_o) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    const int split = blockIdx.x, chunk = blockIdx.y, bg = blockIdx.z;
+    const int split = blockIdx.x, bg = blockIdx.z;
     const int count = dom_count[bg];
-    if (chunk * 128 >= count) return;                            // uniform
+    if (count == 0) return;                                      // uniform
+    // The grid has one y index per 128-row chunk of the longest possible list.  A shorter
+    // list needs fewer chunks; the spare y indices then subdivide every split's token range,
+    // so that a handful of dominant rows still spreads over the whole launch.
+    const RescueLayout lay = rescue_layout(count, m_pad, split_len);
+    const int chunk = blockIdx.y % lay.list_chunks, sub = blockIdx.y / lay.list_chunks;
+    if (sub >= lay.fine) return;                                 // uniform
     const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv;
     const int len = seq_len_of(lens, ragged, b, N);
-    const int t_begin = split * split_len;
-    if (t_begin >= len) return;
-    const int t_end = min(t_begin + split_len, len);
+    const int t_begin = split * split_len + sub * lay.sub_len;
+    const int t_stop = min((split + 1) * split_len, len);
+    if (t_begin >= t_stop) return;
+    const int t_end = min(t_begin + lay.sub_len, t_stop);
 
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int lane = threadIdx.x & 63, half = lane >> 5;
@@ -687,7 +718,7 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_rescue_sweep(const uint16_t 
     const float lrow = lsum + other_half(lsum);
     const int n_top_row = n_top + __shfl_xor(n_top, 32);
     const int top_tok_row = max(top_tok, __shfl_xor(top_tok, 32));
-    const size_t prow = ((size_t)bg * n_splits + split) * m_pad + slot;     // indexed by list position
+    const size_t prow = rescue_partial_row(lay, bg, n_splits, m_pad, split * lay.fine + sub, slot);
     if (half == 0) {
         part_ml[prow * 4 + 0] = lrow;
         part_ml[prow * 4 + 1] = (float)n_top_row;
@@ -724,15 +755,18 @@ __global__ __launch_bounds__(128) void mfma_rescue_combine(const uint16_t *__res
     const int row = dom_rows[(size_t)bg * m_pad + slot];
     const int dd = threadIdx.x;
     const int live_splits = (len + split_len - 1) / split_len;
+    const RescueLayout lay = rescue_layout(dom_count[bg], m_pad, split_len);
     float lrest = 0.f, orest = 0.f, n_top = 0.f;
     int top_tok = -1;
-    for (int s = 0; s < live_splits; ++s) {
-        const size_t prow = ((size_t)bg * n_splits + s) * m_pad + slot;
-        lrest += part_ml[prow * 4 + 0];
-        n_top += part_ml[prow * 4 + 1];
-        top_tok = max(top_tok, __float_as_int(part_ml[prow * 4 + 2]));
-        orest += part_o[prow * kD + dd];
-    }
+    for (int s = 0; s < live_splits; ++s)
+        for (int sub = 0; sub < lay.fine; ++sub) {
+            if (s * split_len + sub * lay.sub_len >= min((s + 1) * split_len, len)) break;   // not swept: no tokens
+            const size_t prow = rescue_partial_row(lay, bg, n_splits, m_pad, s * lay.fine + sub, slot);
+            lrest += part_ml[prow * 4 + 0];
+            n_top += part_ml[prow * 4 + 1];
+            top_tok = max(top_tok, __float_as_int(part_ml[prow * 4 + 2]));
+            orest += part_o[prow * kD + dd];
+        }
     if (n_top != 1.0f || top_tok < 0) return;       // cannot happen for a row above kDominantShare; keep the plain results
     const size_t crow = (size_t)bg * m_pad + row;
     const size_t lo_plane = (size_t)gridDim.y * m_pad * kD;

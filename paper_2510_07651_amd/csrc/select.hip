@@ -261,10 +261,188 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
     }
 }
 
+// ------------------------------------------------------------------------------------
+// Sliced variant for few, long heads: one block per (slice of 8192 tokens, head), five
+// short kernels instead of one long block per head.  The same radix select, with the
+// per-pass histograms written per slice to a workspace and summed by every block of the
+// next kernel (no global atomics, nothing to clear, fixed order of integer sums):
+//   stage 0    histogram of digit 0                               -> hist A
+//   stage 1    pick digit 0 from A;  histogram of digit 1         -> hist B, state
+//   stage 2    pick digit 1 from B;  histogram of digit 2         -> hist A, state
+//   stage 3    pick digit 2 from A = threshold; count (above, equal) per slice -> counts, state
+//   stage 4    ordered emission, each slice starting at the totals of the slices before it
+// ------------------------------------------------------------------------------------
+constexpr int kSliceChunks = 2;
+constexpr int kSliceTok = kSliceChunks * kChunk;          // 8192 tokens per block
+
+struct SliceState {      // per (stage, head), in the workspace: stage k reads slot k-1 and writes slot k
+    uint32_t prefix;     // digits picked so far, in place
+    int remaining;       // rank still to resolve inside the prefix class; after stage 3: how many equal keys are kept
+};
+
+// Sums the slices' histograms of one head into sh.hist (thread t: bins 2t and 2t+1).
+__device__ __forceinline__ void sum_slice_histograms(SelectShared &sh, const int *__restrict__ hist, int n_slices) {
+    const int tid = threadIdx.x;
+    int lo = 0, hi = 0;
+    for (int sl = 0; sl < n_slices; ++sl) {
+        const int2 h = *(const int2 *)(hist + (size_t)sl * kBins + 2 * tid);
+        lo += h.x;
+        hi += h.y;
+    }
+    sh.hist[2 * tid] = lo;
+    sh.hist[2 * tid + 1] = hi;
+}
+
+template <int kStage>
+__global__ __launch_bounds__(kSelThreads) void select_sliced(const float *__restrict__ scores, int N, int budget,
+                                                             int Hkv, int ragged, SeqLens lens, int first, int tail,
+                                                             int radius, int n_slices, int *__restrict__ hist_a,
+                                                             int *__restrict__ hist_b, SliceState *__restrict__ state,
+                                                             int *__restrict__ counts,
+                                                             int32_t *__restrict__ keep_idx) {
+    __shared__ SelectShared sh;
+    const int slice = blockIdx.x, bg = blockIdx.y;
+    const int len = seq_len_of(lens, ragged, bg / Hkv, N);
+    const int cutoff = len - tail;
+    const float *s = scores + (size_t)bg * N;
+    const int tid = threadIdx.x;
+    const int n_chunks = (len + kChunk - 1) / kChunk;     // of the whole head
+    const int c0 = slice * kSliceChunks;                   // first chunk of this slice
+    const bool vec_ok = (((size_t)bg * N) & 3) == 0;
+    // which histogram buffer this stage reads and which it writes
+    const int *hist_in = (kStage == 1 || kStage == 3) ? hist_a : hist_b;
+    int *hist_out = (kStage == 0 || kStage == 2) ? hist_a : hist_b;
+    const SliceState *state_in = state + (size_t)(kStage > 0 ? kStage - 1 : 0) * gridDim.y;
+    SliceState *state_out = state + (size_t)(kStage < 4 ? kStage : 0) * gridDim.y;
+    hist_in += (size_t)bg * n_slices * kBins;
+    hist_out += ((size_t)bg * n_slices + slice) * kBins;
+
+    uint32_t keys[kSliceChunks][kItems];
+#pragma unroll
+    for (int c = 0; c < kSliceChunks; ++c)
+#pragma unroll
+        for (int e = 0; e < kItems; ++e) keys[c][e] = 0u;
+    load_batch<kSliceChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff, radius);
+
+    // ---- the digit the previous stage's histograms decide ----
+    uint32_t prefix = 0, mask = 0;
+    int remaining = budget;
+    if (kStage >= 1 && kStage <= 3) {
+        if (kStage >= 2) { prefix = state_in[bg].prefix; remaining = state_in[bg].remaining; }
+        mask = kStage == 1 ? 0u : (kStage == 2 ? (2047u << 21) : ((2047u << 21) | (2047u << 10)));
+        sum_slice_histograms(sh, hist_in, n_slices);
+        uint32_t digit;
+        pick_digit(sh, remaining, &digit, &remaining);
+        const int shift_prev = kStage == 1 ? 21 : (kStage == 2 ? 10 : 0);
+        prefix |= digit << shift_prev;
+        mask |= (kStage == 3 ? 1023u : 2047u) << shift_prev;
+    }
+    if (kStage == 4) { prefix = state_in[bg].prefix; remaining = state_in[bg].remaining; }
+
+    if (kStage <= 2) {
+        // ---- histogram of this stage's digit over the slice, restricted to the prefix class ----
+        const int shift = kStage == 0 ? 21 : (kStage == 1 ? 10 : 0);
+        const uint32_t dmask = kStage == 2 ? 1023u : 2047u;
+        __syncthreads();
+        sh.hist[2 * tid] = 0;
+        sh.hist[2 * tid + 1] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < kSliceChunks; ++c) {
+            if (c0 + c < n_chunks) {                      // uniform
+#pragma unroll
+                for (int e = 0; e < kItems; ++e) {
+                    const bool in = (c0 + c) * kChunk + tid * kItems + e < len;
+                    histogram_add(sh.hist, (keys[c][e] >> shift) & dmask, in && ((keys[c][e] & mask) == prefix));
+                }
+            }
+        }
+        __syncthreads();
+        *(int2 *)(hist_out + 2 * tid) = make_int2(sh.hist[2 * tid], sh.hist[2 * tid + 1]);
+        if (kStage >= 1 && slice == 0 && tid == 0) { state_out[bg].prefix = prefix; state_out[bg].remaining = remaining; }
+    } else if (kStage == 3) {
+        // ---- threshold known: how many keys of this slice lie above it, how many equal it ----
+        int packed = 0;
+#pragma unroll
+        for (int c = 0; c < kSliceChunks; ++c)
+#pragma unroll
+            for (int e = 0; e < kItems; ++e) {
+                const bool in = (c0 + c) * kChunk + tid * kItems + e < len;
+                packed += (in && keys[c][e] > prefix ? 0x10000 : 0) + (in && keys[c][e] == prefix ? 1 : 0);
+            }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) packed += __shfl_xor(packed, off);
+        __syncthreads();
+        if ((tid & 63) == 0) sh.wave_tot[tid >> 6] = packed;
+        __syncthreads();
+        if (tid == 0) {
+            int tot = 0;
+#pragma unroll
+            for (int w = 0; w < kSelWaves; ++w) tot += sh.wave_tot[w];
+            counts[((size_t)bg * n_slices + slice) * 2 + 0] = tot >> 16;
+            counts[((size_t)bg * n_slices + slice) * 2 + 1] = tot & 0xffff;
+            if (slice == 0) { state_out[bg].prefix = prefix; state_out[bg].remaining = remaining; }
+        }
+    } else {
+        // ---- ordered emission ----
+        int gt_base = 0, eq_base = 0;
+        for (int sl = 0; sl < slice; ++sl) {
+            gt_base += counts[((size_t)bg * n_slices + sl) * 2 + 0];
+            eq_base += counts[((size_t)bg * n_slices + sl) * 2 + 1];
+        }
+        int32_t *out = keep_idx + (size_t)bg * budget;
+#pragma unroll
+        for (int c = 0; c < kSliceChunks; ++c)
+            if (c0 + c < n_chunks)
+                emit_chunk(sh, keys[c], (c0 + c) * kChunk + tid * kItems, len, prefix, remaining, budget, gt_base, eq_base, out);
+    }
+}
+
 }  // namespace
 
+size_t select_workspace_bytes(int B, int Hkv, int N) {
+    const size_t BH = (size_t)B * Hkv;
+    const size_t n_slices = ((size_t)N + kSliceTok - 1) / kSliceTok;
+    auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+    return 2 * up(BH * n_slices * kBins * sizeof(int)) + up(4 * BH * sizeof(SliceState)) + up(BH * n_slices * 2 * sizeof(int));
+}
+
+// Long heads take the sliced path: one block per head keeps a 32K-token head in registers
+// (27 us, about what five launches cost), but beyond that it spills or re-streams the head
+// in every pass (53 us at 64K, 390 us at 128K measured) while the slices stay at 35-55 us.
+bool select_prefers_slices(int B, int Hkv, int N) {
+    const long long BH = (long long)B * Hkv;
+    return N > 8 * kChunk && BH * ((N + kSliceTok - 1) / kSliceTok) <= 2048;
+}
+
+hipError_t launch_select_sliced(const float *scores, int budget, int32_t *keep_idx, int B, int Hkv, int N, int ragged,
+                                const SeqLens &lens, int first, int tail, int radius, void *workspace,
+                                hipStream_t stream) {
+    const size_t BH = (size_t)B * Hkv;
+    const int n_slices = (N + kSliceTok - 1) / kSliceTok;
+    auto up = [](size_t x) { return (x + 255) / 256 * 256; };
+    char *base = (char *)workspace;
+    int *hist_a = (int *)base;                      base += up(BH * n_slices * kBins * sizeof(int));
+    int *hist_b = (int *)base;                      base += up(BH * n_slices * kBins * sizeof(int));
+    SliceState *state = (SliceState *)base;         base += up(4 * BH * sizeof(SliceState));
+    int *counts = (int *)base;
+    const dim3 grid(n_slices, (unsigned)BH), block(kSelThreads);
+#define OBC_SLICED_ARGS scores, N, budget, Hkv, ragged, lens, first, tail, radius, n_slices, hist_a, hist_b, state, counts, keep_idx
+    select_sliced<0><<<grid, block, 0, stream>>>(OBC_SLICED_ARGS);
+    select_sliced<1><<<grid, block, 0, stream>>>(OBC_SLICED_ARGS);
+    select_sliced<2><<<grid, block, 0, stream>>>(OBC_SLICED_ARGS);
+    select_sliced<3><<<grid, block, 0, stream>>>(OBC_SLICED_ARGS);
+    select_sliced<4><<<grid, block, 0, stream>>>(OBC_SLICED_ARGS);
+#undef OBC_SLICED_ARGS
+    return hipGetLastError();
+}
+
 hipError_t launch_select(const float *scores, int budget, int32_t *keep_idx, int B, int Hkv, int N, int ragged,
-                         const SeqLens &lens, int first, int tail, int radius, hipStream_t stream) {
+                         const SeqLens &lens, int first, int tail, int radius, void *workspace,
+                         size_t workspace_bytes, hipStream_t stream) {
+    if (workspace && select_prefers_slices(B, Hkv, N) && workspace_bytes >= select_workspace_bytes(B, Hkv, N))
+        return launch_select_sliced(scores, budget, keep_idx, B, Hkv, N, ragged, lens, first, tail, radius, workspace,
+                                    stream);
     const dim3 grid(B * Hkv), block(kSelThreads);
     if (N <= 8 * kChunk)
         select_topk<8, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, radius, keep_idx);

@@ -76,24 +76,25 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     assert sc(fake, fake, fake, 512, 16, 1, 1, 64, 2, fake, 200, 0, many, fake, 1 << 40, None) == obc.OBC_EUNSUPPORTED
 
     sel = lib.obc_select
-    assert sel(None, 4, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
-    assert sel(fake, 0, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
-    assert sel(fake, 17, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
+    assert sel(None, 4, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EINVAL
+    assert sel(fake, 0, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EINVAL
+    assert sel(fake, 17, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EINVAL
     short = (ctypes.c_int32 * 1)(3)
-    assert sel(fake, 4, fake, 1, 1, 16, short, None) == obc.OBC_EINVAL          # budget > len_b
+    assert sel(fake, 4, fake, 1, 1, 16, short, None, 0, None) == obc.OBC_EINVAL          # budget > len_b
+    assert sel(fake, 4, fake, 1, 1, 16, None, ctypes.c_void_p(4100), 1 << 20, None) == obc.OBC_EWORKSPACE  # misaligned scratch
 
     sp = lib.obc_select_protected          # (scores, num_hh, num_sinks, num_recent, num_coming, keep, B, Hkv, N, lens, stream)
-    assert sp(None, 4, 0, 0, 0, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
-    assert sp(fake, 4, 0, 2, 3, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL         # num_coming > num_recent
-    assert sp(fake, -1, 0, 0, 0, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
-    assert sp(fake, 0, 0, 0, 0, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL         # nothing kept
-    assert sp(fake, 10, 4, 5, 2, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL        # 17 kept of 16
-    assert sp(fake, 2, 1, 1, 0, fake, 1, 1, 16, short, None) == obc.OBC_EINVAL        # 4 kept of len 3
+    assert sp(None, 4, 0, 0, 0, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EINVAL
+    assert sp(fake, 4, 0, 2, 3, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EINVAL         # num_coming > num_recent
+    assert sp(fake, -1, 0, 0, 0, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EINVAL
+    assert sp(fake, 0, 0, 0, 0, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EINVAL         # nothing kept
+    assert sp(fake, 10, 4, 5, 2, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EINVAL        # 17 kept of 16
+    assert sp(fake, 2, 1, 1, 0, fake, 1, 1, 16, short, None, 0, None) == obc.OBC_EINVAL        # 4 kept of len 3
     pl = lib.obc_select_pooled             # (scores, num_hh, num_sinks, num_recent, num_coming, pool, keep, B, Hkv, N, lens, stream)
-    assert pl(fake, 4, 0, 0, 0, 4, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL      # even window
-    assert pl(fake, 4, 0, 0, 0, 0, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
-    assert pl(fake, 4, 0, 0, 0, 17, fake, 1, 1, 16, None, None) == obc.OBC_EUNSUPPORTED
-    assert pl(fake, 17, 0, 0, 0, 5, fake, 1, 1, 16, None, None) == obc.OBC_EINVAL
+    assert pl(fake, 4, 0, 0, 0, 4, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EINVAL      # even window
+    assert pl(fake, 4, 0, 0, 0, 0, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EINVAL
+    assert pl(fake, 4, 0, 0, 0, 17, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EUNSUPPORTED
+    assert pl(fake, 17, 0, 0, 0, 5, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EINVAL
     cs = lib.obc_compact_scores            # (scores, keep, out, B, Hkv, N, budget, N_out, stream)
     assert cs(fake, None, fake, 1, 1, 16, 4, 8, None) == obc.OBC_EINVAL
     assert cs(fake, fake, fake, 1, 1, 16, 4, 3, None) == obc.OBC_EINVAL               # N_out < budget

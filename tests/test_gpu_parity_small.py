@@ -300,3 +300,28 @@ def test_attention_only_and_vatp_scores_match_oracle(name):
         assert err <= tol, "%s %s: err %.3g at %s" % (name, variant, err, where)
         keep = obc.obc_select(gpu, wl.budget, seq_lens=lens).cpu().numpy()
         np.testing.assert_array_equal(keep, oracle.select(g, wl.budget, lens))
+
+
+def test_select_sliced_and_single_block_paths_agree_with_oracle():
+    """Few long heads take the sliced five-kernel path when scratch is available; the one-block-per-head path
+    (workspace=False) must return the same indices, and both the oracle's."""
+    dev = torch.device("cuda")
+    rng = np.random.default_rng(8)
+    cases = [
+        (rng.random((1, 4, 131072)).astype(np.float32) ** 10, dict(num_hh=4096), None),
+        (np.floor(rng.random((2, 3, 50000)) * 3).astype(np.float32), dict(num_hh=20000), [50000, 20001]),   # ties everywhere
+        (rng.standard_normal((1, 1, 32769)).astype(np.float32), dict(num_hh=1, num_sinks=0), None),
+        (rng.random((3, 2, 40000)).astype(np.float32), dict(num_hh=764, num_sinks=4, num_recent=256, pool=5),
+         [40000, 8193, 1024]),
+        (np.zeros((1, 2, 33000), np.float32), dict(num_hh=32999), None),                                     # all equal
+    ]
+    for s, kw, lens in cases:
+        B, H, N = s.shape
+        assert obc.obc_select_workspace_bytes(B, H, N) > 0
+        st = torch.from_numpy(s).to(dev)
+        a = obc.obc_select_pooled(st, seq_lens=lens, **kw).cpu().numpy()
+        b = obc.obc_select_pooled(st, seq_lens=lens, workspace=False, **kw).cpu().numpy()
+        want = oracle.select_pooled(s, seq_lens=lens, **kw)
+        np.testing.assert_array_equal(a, want)
+        np.testing.assert_array_equal(b, want)
+    assert obc.obc_select_workspace_bytes(4, 8, 32768) == 0        # fits one block's registers
