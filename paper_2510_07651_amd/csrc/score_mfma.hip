@@ -758,15 +758,31 @@ __global__ __launch_bounds__(128) void mfma_rescue_combine(const uint16_t *__res
     const RescueLayout lay = rescue_layout(dom_count[bg], m_pad, split_len);
     float lrest = 0.f, orest = 0.f, n_top = 0.f;
     int top_tok = -1;
-    for (int s = 0; s < live_splits; ++s)
-        for (int sub = 0; sub < lay.fine; ++sub) {
-            if (s * split_len + sub * lay.sub_len >= min((s + 1) * split_len, len)) break;   // not swept: no tokens
-            const size_t prow = rescue_partial_row(lay, bg, n_splits, m_pad, s * lay.fine + sub, slot);
-            lrest += part_ml[prow * 4 + 0];
-            n_top += part_ml[prow * 4 + 1];
-            top_tok = max(top_tok, __float_as_int(part_ml[prow * 4 + 2]));
-            orest += part_o[prow * kD + dd];
+    // Sub-ranges are visited in token order, eight at a time with all loads issued before the
+    // first use; a sub-range that starts beyond its split or the sequence was never swept.
+    const int n_sub = live_splits * lay.fine;
+    for (int j0 = 0; j0 < n_sub; j0 += 8) {
+        float4 ml[8];
+        float po[8];
+        bool live[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int j = min(j0 + u, n_sub - 1);
+            const int s = j / lay.fine, sub = j % lay.fine;
+            live[u] = j0 + u < n_sub && s * split_len + sub * lay.sub_len < min((s + 1) * split_len, len);
+            const size_t prow = rescue_partial_row(lay, bg, n_splits, m_pad, j, slot);
+            ml[u] = live[u] ? ((const float4 *)part_ml)[prow] : make_float4(0.f, 0.f, __int_as_float(-1), 0.f);
+            po[u] = live[u] ? part_o[prow * kD + dd] : 0.f;
         }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (!live[u]) continue;
+            lrest += ml[u].x;
+            n_top += ml[u].y;
+            top_tok = max(top_tok, __float_as_int(ml[u].z));
+            orest += po[u];
+        }
+    }
     if (n_top != 1.0f || top_tok < 0) return;       // cannot happen for a row above kDominantShare; keep the plain results
     const size_t crow = (size_t)bg * m_pad + row;
     const size_t lo_plane = (size_t)gridDim.y * m_pad * kD;
