@@ -131,6 +131,39 @@ __device__ __forceinline__ void tile_load_async(const char *__restrict__ head_ba
     }
 }
 
+// The same for one 32-row block (8 KB): two transfers per wave, wave w brings rows 8w .. 8w+7.
+constexpr int kBlkBytes = 32 * kRowBytes;
+template <int SWZ>
+__device__ __forceinline__ void block_lane_offsets(uint32_t (&doff)[2], int wave, int lane) {
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {
+        const int R = (wave * 2 + n) * 4 + (lane >> 4);
+        doff[n] = (uint32_t)(R * kRowBytes + piece_of(SWZ, R, lane & 15) * 16);
+    }
+}
+template <int SWZ>
+__device__ __forceinline__ void block_load_async(const char *__restrict__ head_base, int t0, int last_row,
+                                                 uint32_t lds_block, int wave, int lane, const uint32_t (&doff)[2]) {
+    if (t0 + 31 <= last_row) {                      // uniform: every row of the block exists
+        const char *sbase = head_base + (size_t)t0 * kRowBytes;
+#pragma unroll
+        for (int n = 0; n < 2; ++n) dma16_based(sbase, doff[n], lds_block + (wave * 2 + n) * 1024);
+        return;
+    }
+#pragma unroll
+    for (int n = 0; n < 2; ++n) {                   // rows past the end re-read the last row
+        const int R = (wave * 2 + n) * 4 + (lane >> 4);
+        const int c = piece_of(SWZ, R, lane & 15);
+        int row = t0 + R;
+        row = row > last_row ? last_row : row;
+        dma16(head_base + (size_t)row * kRowBytes + c * 16, lds_block + (wave * 2 + n) * 1024);
+    }
+}
+// Waits until at most kKeep of this wave's most recent transfers are still in flight
+// (transfers complete in issue order; other memory operations in flight only make the wait stricter).
+template <int kKeep>
+__device__ __forceinline__ void wait_async_loads_keep() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kKeep) : "memory"); }
+
 // Per-lane byte offset, inside a kXor16 tile, of piece 2 kk + half of row (lane % 32) of a
 // 32-row block; add 32 * 256 for the tile's second block.  16-byte matrix-core operand:
 // K as the A operand of K Q^T, K and V as B operands of Q K^T and O V^T.
@@ -225,23 +258,23 @@ struct Sweep1Regs {
 template <int PH, bool kMasked, bool kNeedO>
 __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uint32_t lds0, int n, int t_begin,
                                             int t_end, int last_row, int vis, const char *kh, const char *vh,
-                                            const int (&koff)[8], const int (&voff)[4], const uint32_t (&kdoff)[4],
-                                            const uint32_t (&vdoff)[4], int wave, int lane, bool wave_active) {
-    constexpr int kKSlot = (PH == 0 || PH == 3) ? kLdsK0 : kLdsK1;      // tile of block n+1
-    constexpr int kKBlk = (PH == 0 || PH == 2) ? 1 : 0;
-    constexpr int kVSlot = (PH == 1 || PH == 2) ? kLdsV0 : kLdsV1;      // tile of block n-1
-    constexpr int kVBlk = (PH == 0 || PH == 2) ? 1 : 0;
+                                            const int (&koff)[8], const int (&voff)[4], const uint32_t (&kdoff)[2],
+                                            const uint32_t (&vdoff)[2], int wave, int lane, bool wave_active) {
+    // K and V blocks live in rings of four 8 KB slots each (block j in slot j mod 4): K block
+    // n+1 and V block n-1, both started three steps ago, are waited for here while the two
+    // younger batches stay in flight; then K block n+4 and V block n+2 start in the slots
+    // the previous step has finished with.  Blocks past the end of the split are fetched
+    // too (rows clamp to the last one), so that every batch has the same number of transfers.
+    constexpr int kKBase = ((PH + 1) & 3) * kBlkBytes;                  // block n+1
+    constexpr int kVBase = (4 + ((PH + 3) & 3)) * kBlkBytes;            // block n-1
     const float c2 = kLog2e * kInvSqrtD;
     const int half = lane >> 5;
 
-    if (PH & 1) {
-        wait_async_loads();
-        __syncthreads();
-        const int t = (n + 1) >> 1;                     // this step starts K tile t+1 and V tile t
-        const int tk = t_begin + (t + 1) * kTileTok, tv = t_begin + t * kTileTok;
-        if (tk < t_end) tile_load_async<kXor16>(kh, tk, last_row, lds0 + (PH == 1 ? kLdsK0 : kLdsK1), wave, lane, kdoff);
-        if (kNeedO && tv < t_end) tile_load_async<kRot4>(vh, tv, last_row, lds0 + (PH == 1 ? kLdsV1 : kLdsV0), wave, lane, vdoff);
-    }
+    wait_async_loads_keep<kNeedO ? 8 : 4>();
+    __syncthreads();
+    block_load_async<kXor16>(kh, t_begin + (n + 4) * 32, last_row, lds0 + PH * kBlkBytes, wave, lane, kdoff);
+    if (kNeedO)
+        block_load_async<kRot4>(vh, t_begin + (n + 2) * 32, last_row, lds0 + (4 + ((PH + 2) & 3)) * kBlkBytes, wave, lane, vdoff);
     if (!wave_active) return;
     // The running max moved in the previous step: bring the accumulated O^T (blocks <= n-2)
     // to the new reference before block n-1, whose weights already use it, is added.
@@ -259,7 +292,7 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
         for (int ddb = 0; ddb < 4; ++ddb)
 #pragma unroll
             for (int sx = 0; sx < 2; ++sx) {
-                const bf16x8 a = lds_read_vt(smem + kVSlot + (kVBlk * 32 + 16 * sx) * kRowBytes + voff[ddb]);
+                const bf16x8 a = lds_read_vt(smem + kVBase + 16 * sx * kRowBytes + voff[ddb]);
                 R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.phi[sx].v, R.oacc[ddb], 0, 0, 0);
                 R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.plo[sx].v, R.oacc[ddb], 0, 0, 0);
             }
@@ -268,7 +301,7 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
     f32x16 s_next = zero16();
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-        const bf16x8 a = lds_read16(smem + kKSlot + kKBlk * 32 * kRowBytes + koff[kk]);
+        const bf16x8 a = lds_read16(smem + kKBase + koff[kk]);
         s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.q[kk], s_next, 0, 0, 0);
     }
     // ---- vector ALUs: block n ----
@@ -388,22 +421,26 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) settle(R.q[kk]);
 
-    // Prologue: the step before block 0 multiplies zero weights with whatever the second V
-    // tile holds, so that tile is cleared; K tile 0 is fetched and block 0's S^T formed.
-    uint32_t kdoff[4], vdoff[4];
-    tile_lane_offsets<kXor16>(kdoff, wave, lane);
-    tile_lane_offsets<kRot4>(vdoff, wave, lane);
-    for (int e = threadIdx.x; e < kTileBytes / 16; e += kThreads) ((uint4 *)(smem + kLdsV1))[e] = make_uint4(0, 0, 0, 0);
-    tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane, kdoff);
-    wait_async_loads();
+    // Prologue.  Step 0 multiplies zero weights with whatever "V block -1" (slot 3 of the V ring)
+    // holds, so that slot is cleared.  K blocks 0..3 and V blocks 0..1 are started (the batches
+    // the steps -4..-1 would have started), K block 0 is waited for and block 0's S^T formed.
+    uint32_t kdoff[2], vdoff[2];
+    block_lane_offsets<kXor16>(kdoff, wave, lane);
+    block_lane_offsets<kRot4>(vdoff, wave, lane);
+    for (int e = threadIdx.x; e < kBlkBytes / 16; e += kThreads) ((uint4 *)(smem + 7 * kBlkBytes))[e] = make_uint4(0, 0, 0, 0);
+    block_load_async<kXor16>(kh, t_begin, len - 1, lds0, wave, lane, kdoff);
+    block_load_async<kXor16>(kh, t_begin + 32, len - 1, lds0 + kBlkBytes, wave, lane, kdoff);
+    block_load_async<kXor16>(kh, t_begin + 64, len - 1, lds0 + 2 * kBlkBytes, wave, lane, kdoff);
+    if (kNeedO) block_load_async<kRot4>(vh, t_begin, len - 1, lds0 + 4 * kBlkBytes, wave, lane, vdoff);
+    block_load_async<kXor16>(kh, t_begin + 96, len - 1, lds0 + 3 * kBlkBytes, wave, lane, kdoff);
+    if (kNeedO) block_load_async<kRot4>(vh, t_begin + 32, len - 1, lds0 + 5 * kBlkBytes, wave, lane, vdoff);
+    wait_async_loads_keep<kNeedO ? 10 : 6>();         // everything after K block 0 may still be in flight
     __syncthreads();
-    if (t_begin + kTileTok < t_end) tile_load_async<kXor16>(kh, t_begin + kTileTok, len - 1, lds0 + kLdsK1, wave, lane, kdoff);
-    if (kNeedO) tile_load_async<kRot4>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane, vdoff);
     R.s_cur = zero16();
     if (wave_active) {
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
-            const bf16x8 a = lds_read16(smem + kLdsK0 + koff[kk]);
+            const bf16x8 a = lds_read16(smem + koff[kk]);
             R.s_cur = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.q[kk], R.s_cur, 0, 0, 0);
         }
     }
@@ -427,8 +464,9 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
         sweep1_step<3, true, kNeedO>(R, OBC_S1_ARGS); n -= 3;
     }
 #undef OBC_S1_ARGS
+    wait_async_loads();        // the blocks fetched past the end must have landed before the LDS is given back
     if (!wave_active) return;
-    if (kNeedO) {      // drain: P V of the last block (phase 3: second block of the tile in V slot 1)
+    if (kNeedO) {      // drain: P V of the last block (n_total - 1, in slot 3 of the V ring)
         if (R.rescale) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -439,7 +477,7 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
         for (int ddb = 0; ddb < 4; ++ddb)
 #pragma unroll
             for (int sx = 0; sx < 2; ++sx) {
-                const bf16x8 a = lds_read_vt(smem + kLdsV1 + (32 + 16 * sx) * kRowBytes + voff[ddb]);
+                const bf16x8 a = lds_read_vt(smem + 7 * kBlkBytes + 16 * sx * kRowBytes + voff[ddb]);
                 R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.phi[sx].v, R.oacc[ddb], 0, 0, 0);
                 R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.plo[sx].v, R.oacc[ddb], 0, 0, 0);
             }
