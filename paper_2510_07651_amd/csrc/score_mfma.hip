@@ -22,8 +22,9 @@
 // one step are independent, sit in one basic block, and the instruction scheduler
 // interleaves them.  Sweep 2 runs a block's matrix phase and vector phase back to back and
 // leaves the overlap to the second wave on the SIMD (its stationary operands and row
-// constants leave no registers for a second set of accumulators).  K/V tiles of 64 tokens
-// travel HBM -> LDS with direct-to-LDS loads, two steps ahead of their use.
+// constants leave no registers for a second set of accumulators).  K and V travel HBM -> LDS
+// with direct-to-LDS loads: in sweep 1 as 32-token blocks through four-slot rings, three
+// batches in flight; in sweep 2 as 64-token tiles, double-buffered.
 //
 // Precision.  The matrix cores take bf16 operands, and rows whose attention is
 // concentrated on a few keys are sensitive to that rounding (the scores of those keys
@@ -66,7 +67,8 @@ constexpr float kLazyRescale = 8.0f / (kLog2e * kInvSqrtD);   // in raw q.k unit
 // Rows with A_top = 1 / row sum above this share of the attention are rescued (see below).
 constexpr float kDominantShare = 0.9f;
 
-// LDS map (bytes): two K tiles, then two V tiles.
+// LDS map (bytes) of sweep 2 and the rescue sweep: two K tiles, then two V tiles.  Sweep 1 uses
+// the same 64 KB as a ring of four 8 KB K blocks followed by a ring of four V blocks.
 constexpr int kLdsK0 = 0, kLdsK1 = kTileBytes, kLdsV0 = 2 * kTileBytes, kLdsV1 = 3 * kTileBytes;
 constexpr int kLdsTiles = 4 * kTileBytes;           // 64 KB
 
@@ -254,7 +256,8 @@ struct Sweep1Regs {
 // One pipeline step n of sweep 1 (PH = n mod 4 fixes every LDS slot at compile time):
 //   matrix cores: O^T += V^T P^T of block n-1, S^T = K Q^T of block n+1
 //   vector ALUs : online softmax of block n
-// Odd steps first wait for the tiles issued two steps earlier and start the next two.
+// Every step first waits for the two blocks it reads, meets the other waves at a barrier and
+// starts the loads of the blocks three steps ahead.
 template <int PH, bool kMasked, bool kNeedO>
 __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uint32_t lds0, int n, int t_begin,
                                             int t_end, int last_row, int vis, const char *kh, const char *vh,
