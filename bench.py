@@ -103,13 +103,17 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
+    marks[0].record()
     for i in range(args.steps):
         step(i)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = tokens / (ms_per_step * 1e-3)
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))   # device time of each step
 
     # Per-stage device durations (events on the launch stream), same alternating inputs.
     it = max(args.steps, 10)
@@ -184,6 +188,8 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "B": B, "Hq": Hq, "Hkv": Hkv, "d": d, "N": N, "W": W, "budget": wl.budget,
                    "variant": args.variant, "path": "score+select+compact"},
+        "step_ms": {"median": round(per_step[len(per_step) // 2], 4), "min": round(per_step[0], 4),
+                    "max": round(per_step[-1], 4)},
         "head_tokens_per_s": round(head_tokens / (ms_per_step * 1e-3), 1),
         "score_only_tokens_per_s": round(tokens / (ms["obc_score"] * 1e-3), 1),
         "roofline": roofline, "cpu_baseline": cpu,

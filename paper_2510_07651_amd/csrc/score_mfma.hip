@@ -869,7 +869,9 @@ hipError_t launch_rescue(const ScoreArgs &a, const ScoreWorkspace &ws, char *bas
     int32_t *dom_rows = (int32_t *)(base + ws.dom_rows);
     int32_t *dom_count = dom_rows + (size_t)BH * ws.m_pad;
     float *part_ml = (float *)(base + ws.part_ml), *part_o = (float *)(base + ws.part_o);
-    hipError_t e = hipFuncSetAttribute((const void *)mfma_rescue_sweep, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTiles);
+    // The dynamic-LDS limit of a kernel is sticky: raised once per process (one GPU per process).
+    static const hipError_t lds_ok = hipFuncSetAttribute((const void *)mfma_rescue_sweep, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTiles);
+    hipError_t e = lds_ok;
     if (e != hipSuccess) return e;
     mfma_rescue_sweep<<<dim3(ws.splits, ws.n_chunks, BH), dim3(kThreads), kLdsTiles, stream>>>(
         (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens,
@@ -1193,7 +1195,8 @@ template <int kVariant>
 hipError_t launch_sweep2(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStream_t stream) {
     constexpr int nv = kVariant == OBC_ALL ? 3 : 1;
     const size_t lds = kLdsTiles + 256 * sizeof(float) + (size_t)2 * 4 * nv * 64 * sizeof(float);
-    hipError_t e = hipFuncSetAttribute((const void *)mfma_sweep2<kVariant>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    static const hipError_t lds_ok = hipFuncSetAttribute((const void *)mfma_sweep2<kVariant>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipError_t e = lds_ok;
     if (e != hipSuccess) return e;
     const size_t plane_elems = (size_t)a.B * a.Hkv * a.N;
     float *dst = ws.n_chunks > 1 ? (float *)(base + ws.planes) : a.scores;
@@ -1258,8 +1261,9 @@ hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char 
     if (a.stage_mask & OBC_STAGE_SWEEP1) {
         const size_t lds = kLdsTiles;
         const dim3 grid(ws.splits, ws.n_chunks, a.B * a.Hkv);
-        const void *fn = need_o ? (const void *)mfma_sweep1<true> : (const void *)mfma_sweep1<false>;
-        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        static const hipError_t lds_ok_o = hipFuncSetAttribute((const void *)mfma_sweep1<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsTiles);
+        static const hipError_t lds_ok_n = hipFuncSetAttribute((const void *)mfma_sweep1<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsTiles);
+        e = need_o ? lds_ok_o : lds_ok_n;
         if (e != hipSuccess) return e;
         if (need_o)
             mfma_sweep1<true><<<grid, dim3(kThreads), lds, stream>>>(

@@ -325,3 +325,16 @@ def test_select_sliced_and_single_block_paths_agree_with_oracle():
         np.testing.assert_array_equal(a, want)
         np.testing.assert_array_equal(b, want)
     assert obc.obc_select_workspace_bytes(4, 8, 32768) == 0        # fits one block's registers
+
+
+def test_compact_scores_matches_indexing():
+    dev = torch.device("cuda")
+    rng = np.random.default_rng(9)
+    s = rng.standard_normal((3, 2, 1000)).astype(np.float32)
+    idx = np.sort(rng.permuted(np.tile(np.arange(1000), (3, 2, 1)), axis=-1)[..., :77], axis=-1).astype(np.int32)
+    for n_out in (77, 78, 300):
+        out = obc.obc_compact_scores(torch.from_numpy(s).to(dev), torch.from_numpy(idx).to(dev), n_out=n_out).cpu().numpy()
+        np.testing.assert_array_equal(out[..., :77], np.take_along_axis(s, idx, axis=-1))
+        assert np.all(out[..., 77:] == 0.0) and out.shape == (3, 2, n_out)
+    with pytest.raises(obc.ObcError):
+        obc.obc_compact_scores(torch.from_numpy(s).to(dev), torch.from_numpy(idx).to(dev), n_out=10)
