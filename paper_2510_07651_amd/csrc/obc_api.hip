@@ -67,7 +67,7 @@ using namespace obc;
 
 extern "C" {
 
-int obc_version(void) { return 100; }
+int obc_version(void) { return 101; }
 
 const char *obc_status_string(int status) {
     switch (status) {
