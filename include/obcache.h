@@ -16,7 +16,9 @@
  *
  * General conventions
  *   - Every data pointer is a DEVICE pointer owned by the caller unless its name
- *     ends in `_host`.  Tensors are contiguous, row-major, in the stated shape.
+ *     ends in `_host`.  Tensors are contiguous, row-major, in the stated shape;
+ *     q, k, v and the compacted outputs start on 16-byte boundaries (OBC_EINVAL
+ *     otherwise), fp32 and int32 arrays on 4-byte boundaries.
  *   - Nothing here allocates, frees or synchronises.  All work is enqueued on
  *     `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).
  *     Outputs are valid once that stream has reached the end of the call's work.

@@ -119,6 +119,7 @@ static int score_impl(const void *q, const void *k, const void *v, int N, int W,
                       float *scores, int B, int dtype, const int32_t *seq_lens_host, void *workspace,
                       size_t workspace_bytes, void *hip_stream, int stage_mask, int accumulate) {
     if (!q || !k || !v || !scores) return OBC_EINVAL;
+    if ((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v) & 15) != 0 || ((uintptr_t)scores & 3) != 0) return OBC_EINVAL;
     if (stage_mask < 1 || stage_mask > OBC_STAGE_ALL) return OBC_EINVAL;
     ScoreWorkspace ws;
     int rc = plan_score_workspace(B, N, W, Hq, Hkv, d, dtype, variant, &ws);
@@ -186,6 +187,7 @@ int obc_select(const float *scores, int budget, int32_t *keep_idx, int B, int Hk
 int obc_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_out, void *v_out, int B, int Hkv,
                 int N, int budget, int d, int dtype, void *hip_stream) {
     if (!k || !v || !keep_idx || !k_out || !v_out) return OBC_EINVAL;
+    if ((((uintptr_t)k | (uintptr_t)v | (uintptr_t)k_out | (uintptr_t)v_out) & 15) != 0) return OBC_EINVAL;
     if (B < 1 || Hkv < 1 || N < 1 || budget < 1 || d < 1) return OBC_EINVAL;
     if (dtype != OBC_F32 && dtype != OBC_BF16) return OBC_EUNSUPPORTED;
     const long long row_bytes = (long long)d * (dtype == OBC_F32 ? 4 : 2);

@@ -191,7 +191,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
     int32_t *out = keep_idx + (size_t)bg * budget;
     const int tid = threadIdx.x;
     const int n_chunks = (len + kChunk - 1) / kChunk;
-    const bool vec_ok = (((size_t)bg * N) & 3) == 0;      // the head starts on a 16-byte boundary
+    const bool vec_ok = ((size_t)s & 15) == 0;            // the head starts on a 16-byte boundary
 
     uint32_t keys[kRegChunks][kItems];
 #pragma unroll
@@ -308,7 +308,7 @@ __global__ __launch_bounds__(kSelThreads) void select_sliced(const float *__rest
     const int tid = threadIdx.x;
     const int n_chunks = (len + kChunk - 1) / kChunk;     // of the whole head
     const int c0 = slice * kSliceChunks;                   // first chunk of this slice
-    const bool vec_ok = (((size_t)bg * N) & 3) == 0;
+    const bool vec_ok = ((size_t)s & 15) == 0;
     // which histogram buffer this stage reads and which it writes
     const int *hist_in = (kStage == 1 || kStage == 3) ? hist_a : hist_b;
     int *hist_out = (kStage == 0 || kStage == 2) ? hist_a : hist_b;

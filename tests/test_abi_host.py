@@ -61,6 +61,8 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     sc = lib.obc_score
     assert sc(None, fake, fake, 512, 16, 1, 1, 64, 2, fake, 1, 0, None, fake, 1 << 30, None) == obc.OBC_EINVAL
     assert sc(fake, fake, fake, 512, 16, 1, 1, 64, 2, None, 1, 0, None, fake, 1 << 30, None) == obc.OBC_EINVAL
+    odd = ctypes.c_void_p(4104)           # 8-byte aligned only
+    assert sc(fake, odd, fake, 512, 16, 1, 1, 64, 2, fake, 1, 0, None, fake, 1 << 30, None) == obc.OBC_EINVAL
     # W > len_b for the second sequence
     assert sc(fake, fake, fake, 512, 16, 1, 1, 64, 2, fake, 2, 0, lens, fake, 1 << 30, None) == obc.OBC_EINVAL
     # len_b > N
@@ -105,5 +107,6 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     cp = lib.obc_compact
     assert cp(fake, fake, None, fake, fake, 1, 1, 16, 4, 64, 0, None) == obc.OBC_EINVAL
     assert cp(fake, fake, fake, fake, fake, 1, 1, 16, 0, 64, 0, None) == obc.OBC_EINVAL
+    assert cp(fake, fake, fake, ctypes.c_void_p(4104), fake, 1, 1, 16, 4, 64, 0, None) == obc.OBC_EINVAL   # misaligned output
     assert cp(fake, fake, fake, fake, fake, 1, 1, 16, 4, 6, 1, None) == obc.OBC_EUNSUPPORTED   # 12-byte rows
     assert cp(fake, fake, fake, fake, fake, 1, 1, 16, 4, 64, 9, None) == obc.OBC_EUNSUPPORTED  # dtype

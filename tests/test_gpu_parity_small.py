@@ -338,3 +338,18 @@ def test_compact_scores_matches_indexing():
         assert np.all(out[..., 77:] == 0.0) and out.shape == (3, 2, n_out)
     with pytest.raises(obc.ObcError):
         obc.obc_compact_scores(torch.from_numpy(s).to(dev), torch.from_numpy(idx).to(dev), n_out=10)
+
+
+def test_select_on_scores_that_start_off_a_16_byte_boundary():
+    """A view into a larger buffer: only 4-byte aligned, so the kernels must not use their 128-bit loads."""
+    dev = torch.device("cuda")
+    rng = np.random.default_rng(10)
+    for shape, budget in (((2, 3, 5001), 300), ((1, 2, 40003), 4000)):
+        s = rng.random(shape).astype(np.float32)
+        buf = torch.zeros(s.size + 3, dtype=torch.float32, device=dev)
+        for off in (1, 3):
+            view = buf[off:off + s.size].view(shape)
+            view.copy_(torch.from_numpy(s))
+            assert view.data_ptr() % 16 != 0
+            keep = obc.obc_select(view, budget).cpu().numpy()
+            np.testing.assert_array_equal(keep, oracle.select(s, budget))
