@@ -110,3 +110,12 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     assert cp(fake, fake, fake, ctypes.c_void_p(4104), fake, 1, 1, 16, 4, 64, 0, None) == obc.OBC_EINVAL   # misaligned output
     assert cp(fake, fake, fake, fake, fake, 1, 1, 16, 4, 6, 1, None) == obc.OBC_EUNSUPPORTED   # 12-byte rows
     assert cp(fake, fake, fake, fake, fake, 1, 1, 16, 4, 64, 9, None) == obc.OBC_EUNSUPPORTED  # dtype
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU per box in this build: bench.py says so and exits instead of launching collectives."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
