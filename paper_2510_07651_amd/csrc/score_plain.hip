@@ -166,7 +166,7 @@ __global__ __launch_bounds__(kThreads) void plain_window_attention(
         if (tok == 0 && rq + 4 * i < W) ls[rq + 4 * i] = s;
     }
     __syncthreads();
-    if (threadIdx.x < W) {
+    if ((int)threadIdx.x < W) {
         const size_t row = (size_t)bh * W + threadIdx.x;
         const float lr = ls[threadIdx.x];
         row_max[row] = ms[threadIdx.x];
