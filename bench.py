@@ -141,10 +141,13 @@ def main():
     achieved = algo_bytes / (ms["obc_score"] * 1e-3) / 1e9
     mfma_flops = 4 * 2 * Hq * W * d * tokens
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.json" % wl.name)
+    # measured HBM bytes of one obc_score call, from the committed counter summary of this workload
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % wl.name)
     if os.path.exists(tpath):
+        import re
         with open(tpath) as f:
-            traffic = json.load(f).get("obc_score_bytes_per_call")
+            m = re.search(r"obc_score \(all mfma_\* kernels\):.*?=\s*(\d+) bytes per call", f.read())
+        traffic = int(m.group(1)) if m else None
     roofline = {
         "bound": "hbm", "kernel": "obc_score = mfma_sweep1 + mfma_combine + mfma_sweep2",
         "achieved": round(achieved, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
