@@ -187,11 +187,33 @@ int obc_select_pooled(const float *scores, int num_hh, int num_sinks, int num_re
                       void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Head-adaptive selection (Appendix C, "AdaKV": head-wise budgets from a global ranking of
+ * the scores across all heads of the layer, with a safeguard, 0.2 in the paper's
+ * experiments).  Per sequence the layer keeps Hkv * budget tokens: every KV head first
+ * keeps its own n_safe best (the safeguard; floor(0.2 * budget) reproduces the paper's
+ * setting), and the remaining Hkv * (budget - n_safe) slots go to the highest scores among
+ * all other live (head, token) pairs; equal scores are won by the lower head, then the
+ * lower index.  Outputs, per (b, KV head):
+ *   counts    [B, Hkv] int32       tokens kept by this head (their sum over the heads of a
+ *                                  sequence is Hkv * budget)
+ *   keep_idx  [B, Hkv, cap] int32  their indices, ascending, followed by -1
+ * `cap` must hold the most one head can receive, min(len_b, Hkv*budget - (Hkv-1)*n_safe).
+ * obc_compact turns the -1 entries into all-zero rows.  n_safe = budget is obc_select.
+ * Requires 0 <= n_safe <= budget <= len_b and a workspace of
+ * obc_select_adaptive_workspace_bytes(...) bytes, 256-byte aligned.
+ */
+int obc_select_adaptive_workspace_bytes(int B, int Hkv, int N, int budget, int n_safe, size_t *bytes_out);
+int obc_select_adaptive(const float *scores, int budget, int n_safe, int32_t *keep_idx, int32_t *counts, int cap,
+                        int B, int Hkv, int N, const int32_t *seq_lens_host,
+                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Compaction (Algorithm 2's gather; with indices from obc_select_protected the recent rows come along):
  *   k_out[b,g,j,:] = k[b,g,keep_idx[b,g,j],:]   and the same for v.
  *   k, v          [B, Hkv, N, d] of `dtype`
- *   keep_idx      [B, Hkv, budget] int32, every entry in [0, N)  (device; not
- *                 checked on the host -- entries outside [0, N) are clamped)
+ *   keep_idx      [B, Hkv, budget] int32, entries in [0, N), or -1 for an all-zero
+ *                 output row (the padding of obc_select_adaptive's lists).  Device data,
+ *                 not checked on the host: entries >= N are clamped to N-1.
  *   k_out, v_out  [B, Hkv, budget, d]; must not overlap k, v.
  * d * element size must be a multiple of 16 bytes.
  */

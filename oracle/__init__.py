@@ -10,7 +10,9 @@ from .binding import (  # noqa: F401
     compact,
     num_threads,
     score,
+    adaptive_cap,
     select,
+    select_adaptive,
     select_pooled,
     select_protected,
     vatp_score,

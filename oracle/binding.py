@@ -58,6 +58,8 @@ def _load():
         lib.obc_oracle_select_protected.argtypes = [fp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, ip, ip]
         lib.obc_oracle_select_pooled.restype = c_int
         lib.obc_oracle_select_pooled.argtypes = [fp, c_int, c_int, c_int, c_int, c_int, c_int, c_int, c_int, ip, ip]
+        lib.obc_oracle_select_adaptive.restype = c_int
+        lib.obc_oracle_select_adaptive.argtypes = [fp, c_int, c_int, c_int, c_int, c_int, c_int, ip, ip, ip]
         lib.obc_oracle_compact.restype = c_int
         lib.obc_oracle_compact.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ip, c_int, c_int, c_int, c_int,
                                            ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p]
@@ -194,6 +196,30 @@ def select_pooled(scores, num_hh: int, pool: int = 5, num_sinks: int = 0, num_re
                                           out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
     _check(rc, "select_pooled")
     return out
+
+
+def adaptive_cap(Hkv: int, budget: int, n_safe: int, max_len: int) -> int:
+    """The most tokens one head can receive: everything beyond the other heads' safeguards."""
+    return int(min(max_len, Hkv * budget - (Hkv - 1) * n_safe))
+
+
+def select_adaptive(scores, budget: int, n_safe: int, cap=None, seq_lens=None):
+    """(keep_idx [B,Hkv,cap] int32 ascending then -1, counts [B,Hkv] int32): head-adaptive budgets."""
+    if hasattr(scores, "detach"):
+        scores = scores.detach().cpu().numpy()
+    s = np.ascontiguousarray(scores, dtype=np.float32)
+    B, Hkv, N = s.shape
+    keep, lp = _lens(seq_lens, B)
+    if cap is None:
+        cap = adaptive_cap(Hkv, budget, n_safe, N if seq_lens is None else max(seq_lens))
+    out = np.empty((B, Hkv, max(int(cap), 0)), dtype=np.int32)
+    counts = np.empty((B, Hkv), dtype=np.int32)
+    rc = _load().obc_oracle_select_adaptive(s.ctypes.data_as(ctypes.POINTER(ctypes.c_float)), B, Hkv, N, int(budget),
+                                            int(n_safe), int(cap), lp,
+                                            out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                            counts.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+    _check(rc, "select_adaptive")
+    return out, counts
 
 
 def compact(k: np.ndarray, v: np.ndarray, keep_idx: np.ndarray):

@@ -411,9 +411,82 @@ int obc_oracle_select_pooled(const float *scores, int B, int Hkv, int N, int num
 }
 
 /*
+ * Head-adaptive selection (Appendix C, "AdaKV": the head-wise budgets follow from ranking
+ * the eviction scores globally across all heads of the layer, with a safeguard that is
+ * 0.2 in the paper's experiments).  Reading taken here, per sequence b:
+ *   - the layer keeps Hkv * budget tokens in total;
+ *   - every KV head first keeps its own n_safe highest-scoring tokens (the safeguard:
+ *     n_safe = floor(0.2 * budget) in the paper's setting), ties to the lowest index;
+ *   - the remaining Hkv * (budget - n_safe) slots go to the highest scores among all other
+ *     live (head, token) pairs of the sequence, ties to the lower head, then the lower index.
+ * Output per (b, g): counts[b,g] kept tokens, their indices ascending in
+ * keep_idx[b,g,0..count), then -1 up to `cap` entries.  n_safe = budget is the per-head
+ * selection of obc_oracle_select; n_safe = 0 is a plain global top-k.
+ */
+typedef struct { float s; int32_t g; int32_t p; } scored3_t;
+static int cmp_scored3(const void *a, const void *b)
+{
+    const scored3_t *x = (const scored3_t *)a, *y = (const scored3_t *)b;
+    scored_t sx = { x->s, 0 }, sy = { y->s, 0 };
+    int c = cmp_scored(&sx, &sy);              /* score order incl. NaN lowest, -0 == +0; 0 on equal scores */
+    if (c) return c;
+    if (x->g != y->g) return x->g < y->g ? -1 : 1;
+    return x->p < y->p ? -1 : (x->p > y->p ? 1 : 0);
+}
+
+int obc_oracle_select_adaptive(const float *scores, int B, int Hkv, int N, int budget, int n_safe, int cap,
+                               const int32_t *seq_lens, int32_t *keep_idx, int32_t *counts)
+{
+    if (B < 1 || Hkv < 1 || N < 1 || budget < 1 || n_safe < 0 || n_safe > budget || cap < 1) return OBC_ORACLE_EINVAL;
+    for (int b = 0; b < B; ++b) {
+        int len = seq_len_of(seq_lens, b, N);
+        if (len > N || budget > len) return OBC_ORACLE_EINVAL;
+        long long most = (long long)Hkv * budget - (long long)(Hkv - 1) * n_safe;   /* the most one head can get */
+        if (most > len) most = len;
+        if (cap < most) return OBC_ORACLE_EINVAL;
+    }
+    scored_t *tmp = (scored_t *)malloc(sizeof(scored_t) * (size_t)N);
+    scored3_t *rest = (scored3_t *)malloc(sizeof(scored3_t) * (size_t)Hkv * N);
+    unsigned char *kept = (unsigned char *)malloc((size_t)Hkv * N);
+    for (int b = 0; b < B; ++b) {
+        const int len = seq_len_of(seq_lens, b, N);
+        memset(kept, 0, (size_t)Hkv * N);
+        for (int g = 0; g < Hkv; ++g) {                       /* the safeguard: each head's own top n_safe */
+            const float *s = scores + ((size_t)b * Hkv + g) * N;
+            for (int p = 0; p < len; ++p) { tmp[p].s = s[p]; tmp[p].p = p; }
+            qsort(tmp, (size_t)len, sizeof(scored_t), cmp_scored);
+            for (int j = 0; j < n_safe; ++j) kept[(size_t)g * N + tmp[j].p] = 1;
+        }
+        size_t m = 0;                                          /* everything else competes globally */
+        for (int g = 0; g < Hkv; ++g)
+            for (int p = 0; p < len; ++p)
+                if (!kept[(size_t)g * N + p]) {
+                    rest[m].s = scores[((size_t)b * Hkv + g) * N + p];
+                    rest[m].g = g;
+                    rest[m].p = p;
+                    ++m;
+                }
+        qsort(rest, m, sizeof(scored3_t), cmp_scored3);
+        const size_t extra = (size_t)Hkv * (size_t)(budget - n_safe);
+        for (size_t j = 0; j < extra; ++j) kept[(size_t)rest[j].g * N + rest[j].p] = 1;
+        for (int g = 0; g < Hkv; ++g) {
+            int32_t *out = keep_idx + ((size_t)b * Hkv + g) * cap;
+            int n = 0;
+            for (int p = 0; p < len; ++p)
+                if (kept[(size_t)g * N + p]) out[n++] = p;
+            counts[(size_t)b * Hkv + g] = n;
+            for (int j = n; j < cap; ++j) out[j] = -1;
+        }
+    }
+    free(tmp); free(rest); free(kept);
+    return OBC_ORACLE_OK;
+}
+
+/*
  * Row gather (Algorithm 2 without the recent-window tail):
  *   k_out[b,g,j,:] = k[b,g,keep_idx[b,g,j],:], same for v.  Rows are
- *   row_bytes = d * element size bytes long.
+ *   row_bytes = d * element size bytes long.  An index of -1 (the padding of the
+ *   ragged lists of obc_oracle_select_adaptive) gives an all-zero row.
  */
 int obc_oracle_compact(const void *k, const void *v, const int32_t *keep_idx,
                        int B, int Hkv, int N, int budget, size_t row_bytes,
@@ -423,8 +496,14 @@ int obc_oracle_compact(const void *k, const void *v, const int32_t *keep_idx,
     for (int bg = 0; bg < B * Hkv; ++bg)
         for (int j = 0; j < budget; ++j) {
             int32_t p = keep_idx[(size_t)bg * budget + j];
-            if (p < 0 || p >= N) return OBC_ORACLE_EINVAL;
-            size_t src = ((size_t)bg * N + p) * row_bytes, dst = ((size_t)bg * budget + j) * row_bytes;
+            if (p >= N) return OBC_ORACLE_EINVAL;
+            size_t dst = ((size_t)bg * budget + j) * row_bytes;
+            if (p < 0) {                                   /* padding of a ragged index list: an all-zero row */
+                memset((char *)k_out + dst, 0, row_bytes);
+                memset((char *)v_out + dst, 0, row_bytes);
+                continue;
+            }
+            size_t src = ((size_t)bg * N + p) * row_bytes;
             memcpy((char *)k_out + dst, (const char *)k + src, row_bytes);
             memcpy((char *)v_out + dst, (const char *)v + src, row_bytes);
         }

@@ -64,6 +64,11 @@ def load_library():
     lib.obc_select_pooled.restype = c_int
     lib.obc_select_pooled.argtypes = [c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p, c_int, c_int, c_int, i32p,
                                       c_void_p, c_size_t, c_void_p]
+    lib.obc_select_adaptive_workspace_bytes.restype = c_int
+    lib.obc_select_adaptive_workspace_bytes.argtypes = [c_int, c_int, c_int, c_int, c_int, ctypes.POINTER(c_size_t)]
+    lib.obc_select_adaptive.restype = c_int
+    lib.obc_select_adaptive.argtypes = [c_void_p, c_int, c_int, c_void_p, c_void_p, c_int, c_int, c_int, c_int, i32p,
+                                        c_void_p, c_size_t, c_void_p]
     lib.obc_compact.restype = c_int
     lib.obc_compact.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int,
                                 c_int, c_void_p]
@@ -244,6 +249,32 @@ def obc_select_pooled(scores: torch.Tensor, num_hh: int, pool: int = 5, num_sink
     if rc != OBC_OK:
         raise ObcError(rc, "obc_select_pooled")
     return keep_idx
+
+
+def obc_select_adaptive(scores: torch.Tensor, budget: int, n_safe: int, cap: Optional[int] = None, seq_lens=None,
+                        workspace: Optional[torch.Tensor] = None):
+    """Head-adaptive budgets: (keep_idx [B,Hkv,cap] int32 ascending then -1, counts [B,Hkv] int32)."""
+    _require_cuda(scores)
+    if scores.dtype != torch.float32 or scores.dim() != 3:
+        raise ValueError("scores must be [B,Hkv,N] float32")
+    B, Hkv, N = scores.shape
+    if cap is None:
+        longest = N if seq_lens is None else max(int(x) for x in seq_lens)
+        cap = min(longest, Hkv * int(budget) - (Hkv - 1) * int(n_safe))
+    if workspace is None:
+        need = ctypes.c_size_t(0)
+        rc = load_library().obc_select_adaptive_workspace_bytes(B, Hkv, N, int(budget), int(n_safe), ctypes.byref(need))
+        if rc != OBC_OK:
+            raise ObcError(rc, "obc_select_adaptive_workspace_bytes")
+        workspace = torch.empty(max(int(need.value), 256), dtype=torch.uint8, device=scores.device)
+    keep_idx = torch.empty((B, Hkv, max(int(cap), 0)), dtype=torch.int32, device=scores.device)
+    counts = torch.empty((B, Hkv), dtype=torch.int32, device=scores.device)
+    rc = load_library().obc_select_adaptive(scores.data_ptr(), int(budget), int(n_safe), keep_idx.data_ptr(),
+                                            counts.data_ptr(), int(cap), B, Hkv, N, _lens_arg(seq_lens, B),
+                                            workspace.data_ptr(), workspace.numel(), _stream_ptr(scores))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_select_adaptive")
+    return keep_idx, counts
 
 
 def obc_compact(k: torch.Tensor, v: torch.Tensor, keep_idx: torch.Tensor, k_out=None, v_out=None):

@@ -15,10 +15,14 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4 *__restrict__ k, 
     const int c = (int)(t % row_vec);
     const size_t bg = out_row / budget;
     int p = keep_idx[out_row];
-    p = p < 0 ? 0 : (p >= N ? N - 1 : p);
+    uint4 *out = blockIdx.y == 0 ? k_out : v_out;
+    if (p < 0) {                                    // padding of a ragged index list: an all-zero row
+        out[t] = make_uint4(0, 0, 0, 0);
+        return;
+    }
+    p = p >= N ? N - 1 : p;
     const size_t src = (bg * N + p) * row_vec + c;
     const uint4 *in = blockIdx.y == 0 ? k : v;
-    uint4 *out = blockIdx.y == 0 ? k_out : v_out;
     out[t] = in[src];
 }
 

@@ -60,7 +60,11 @@ hipError_t launch_score_plain(const ScoreArgs &a, const ScoreWorkspace &ws, char
 hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char *ws_base, hipStream_t stream);
 hipError_t launch_select(const float *scores, int budget, int32_t *keep_idx, int B, int Hkv, int N, int ragged,
                          const SeqLens &lens, int first, int tail, int radius, void *workspace,
-                         size_t workspace_bytes, hipStream_t stream);
+                         size_t workspace_bytes, hipStream_t stream, int keys_in = 0);
+size_t select_adaptive_workspace_bytes(int B, int Hkv, int N, int budget, int n_safe);
+hipError_t launch_select_adaptive(const float *scores, int budget, int n_safe, int cap, int32_t *keep_idx,
+                                  int32_t *counts, int B, int Hkv, int N, int ragged, const SeqLens &lens,
+                                  void *workspace, hipStream_t stream);
 size_t select_workspace_bytes(int B, int Hkv, int N);
 bool select_prefers_slices(int B, int Hkv, int N);
 hipError_t launch_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_out, void *v_out, int B,

@@ -184,6 +184,45 @@ int obc_select(const float *scores, int budget, int32_t *keep_idx, int B, int Hk
                              workspace_bytes, hip_stream);
 }
 
+static int adaptive_checks(int budget, int n_safe, int cap, int B, int Hkv, int N, const int32_t *seq_lens_host,
+                           int *ragged, SeqLens *lens) {
+    if (B < 1 || Hkv < 1 || N < 1 || budget < 1 || n_safe < 0 || n_safe > budget || budget > N) return OBC_EINVAL;
+    if ((long long)B * Hkv > 0x7fffffffLL / 2 || (long long)Hkv * N > (1LL << 30)) return OBC_EUNSUPPORTED;
+    const int rc = fill_lens(seq_lens_host, B, N, budget, ragged, lens);
+    if (rc != OBC_OK) return rc;
+    for (int b = 0; b < B; ++b) {          // the most one head can receive must fit its index list
+        const long long len = *ragged ? lens->len[b] : N;
+        long long most = (long long)Hkv * budget - (long long)(Hkv - 1) * n_safe;
+        if (most > len) most = len;
+        if (cap < most) return OBC_EINVAL;
+    }
+    return OBC_OK;
+}
+
+int obc_select_adaptive_workspace_bytes(int B, int Hkv, int N, int budget, int n_safe, size_t *bytes_out) {
+    if (!bytes_out || B < 1 || Hkv < 1 || N < 1 || budget < 1 || n_safe < 0 || n_safe > budget || budget > N) return OBC_EINVAL;
+    if ((long long)B * Hkv > 0x7fffffffLL / 2 || (long long)Hkv * N > (1LL << 30)) return OBC_EUNSUPPORTED;
+    *bytes_out = select_adaptive_workspace_bytes(B, Hkv, N, budget, n_safe);
+    return OBC_OK;
+}
+
+int obc_select_adaptive(const float *scores, int budget, int n_safe, int32_t *keep_idx, int32_t *counts, int cap,
+                        int B, int Hkv, int N, const int32_t *seq_lens_host, void *workspace, size_t workspace_bytes,
+                        void *hip_stream) {
+    if (!scores || !keep_idx || !counts) return OBC_EINVAL;
+    int ragged = 0;
+    SeqLens lens;
+    std::memset(&lens, 0, sizeof(lens));
+    const int rc = adaptive_checks(budget, n_safe, cap, B, Hkv, N, seq_lens_host, &ragged, &lens);
+    if (rc != OBC_OK) return rc;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 ||
+        workspace_bytes < select_adaptive_workspace_bytes(B, Hkv, N, budget, n_safe))
+        return OBC_EWORKSPACE;
+    const hipError_t e = launch_select_adaptive(scores, budget, n_safe, cap, keep_idx, counts, B, Hkv, N, ragged, lens,
+                                                workspace, (hipStream_t)hip_stream);
+    return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
+}
+
 int obc_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_out, void *v_out, int B, int Hkv,
                 int N, int budget, int d, int dtype, void *hip_stream) {
     if (!k || !v || !keep_idx || !k_out || !v_out) return OBC_EINVAL;

@@ -23,6 +23,8 @@
 //
 // Heads of up to 65536 tokens are read from memory once (128-bit loads) and their keys
 // stay in registers for all passes; longer heads are streamed again in every pass.
+#include <cstring>
+
 #include "internal.h"
 
 namespace obc {
@@ -138,7 +140,8 @@ __device__ __forceinline__ void emit_chunk(SelectShared &sh, const uint32_t (&ke
 // Keys of chunks c0 .. c0 + kRegChunks - 1 of one head (128-bit loads where possible).
 template <int kRegChunks>
 __device__ __forceinline__ void load_batch(uint32_t (&keys)[kRegChunks][kItems], const float *__restrict__ s, int c0,
-                                           int n_chunks, int len, bool vec_ok, int first, int cutoff, int radius) {
+                                           int n_chunks, int len, bool vec_ok, int first, int cutoff, int radius,
+                                           bool keys_in = false) {
 #pragma unroll
     for (int c = 0; c < kRegChunks; ++c) {
         if (c0 + c < n_chunks) {                          // uniform
@@ -159,6 +162,10 @@ __device__ __forceinline__ void load_batch(uint32_t (&keys)[kRegChunks][kItems],
                         if (j <= 2 * radius) sum = __fadd_rn(sum, w[e + j]);
                     keys[c][e] = i0 + e < len ? order_key(sum) : 0u;
                 }
+            } else if (keys_in) {                         // uniform: the input already holds order-preserving keys
+                const uint32_t *kin = (const uint32_t *)s;
+#pragma unroll
+                for (int e = 0; e < kItems; ++e) keys[c][e] = i0 + e < len ? kin[i0 + e] : 0u;
             } else if (vec_ok && i0 + kItems <= len) {
                 const float4 f = *(const float4 *)(s + i0);
                 keys[c][0] = order_key(f.x); keys[c][1] = order_key(f.y);
@@ -182,7 +189,7 @@ __device__ __forceinline__ void load_batch(uint32_t (&keys)[kRegChunks][kItems],
 template <int kRegChunks, bool kResident>
 __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restrict__ scores, int N, int budget,
                                                            int Hkv, int ragged, SeqLens lens, int first, int tail,
-                                                           int radius, int32_t *__restrict__ keep_idx) {
+                                                           int radius, int keys_in, int32_t *__restrict__ keep_idx) {
     __shared__ SelectShared sh;
     const int bg = blockIdx.x;
     const int len = seq_len_of(lens, ragged, bg / Hkv, N);
@@ -198,7 +205,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
     for (int c = 0; c < kRegChunks; ++c)
 #pragma unroll
         for (int e = 0; e < kItems; ++e) keys[c][e] = 0u;
-    if (kResident) load_batch<kRegChunks>(keys, s, 0, n_chunks, len, vec_ok, first, cutoff, radius);
+    if (kResident) load_batch<kRegChunks>(keys, s, 0, n_chunks, len, vec_ok, first, cutoff, radius, keys_in != 0);
 
     // ---- radix select: key of the budget-th largest element ----
     uint32_t prefix = 0, mask = 0;
@@ -222,7 +229,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
             }
         } else {
             for (int c0 = 0; c0 < n_chunks; c0 += kRegChunks) {
-                load_batch<kRegChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff, radius);
+                load_batch<kRegChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff, radius, keys_in != 0);
 #pragma unroll
                 for (int c = 0; c < kRegChunks; ++c) {
                     if (c0 + c < n_chunks) {              // uniform
@@ -252,7 +259,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
                 emit_chunk(sh, keys[c], c * kChunk + tid * kItems, len, thr, need_eq, budget, gt_base, eq_base, out);
     } else {
         for (int c0 = 0; c0 < n_chunks; c0 += kRegChunks) {
-            load_batch<kRegChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff, radius);
+            load_batch<kRegChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff, radius, keys_in != 0);
 #pragma unroll
             for (int c = 0; c < kRegChunks; ++c)
                 if (c0 + c < n_chunks)
@@ -296,7 +303,7 @@ __device__ __forceinline__ void sum_slice_histograms(SelectShared &sh, const int
 template <int kStage>
 __global__ __launch_bounds__(kSelThreads) void select_sliced(const float *__restrict__ scores, int N, int budget,
                                                              int Hkv, int ragged, SeqLens lens, int first, int tail,
-                                                             int radius, int n_slices, int *__restrict__ hist_a,
+                                                             int radius, int keys_in, int n_slices, int *__restrict__ hist_a,
                                                              int *__restrict__ hist_b, SliceState *__restrict__ state,
                                                              int *__restrict__ counts,
                                                              int32_t *__restrict__ keep_idx) {
@@ -322,7 +329,7 @@ __global__ __launch_bounds__(kSelThreads) void select_sliced(const float *__rest
     for (int c = 0; c < kSliceChunks; ++c)
 #pragma unroll
         for (int e = 0; e < kItems; ++e) keys[c][e] = 0u;
-    load_batch<kSliceChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff, radius);
+    load_batch<kSliceChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff, radius, keys_in != 0);
 
     // ---- the digit the previous stage's histograms decide ----
     uint32_t prefix = 0, mask = 0;
@@ -398,7 +405,102 @@ __global__ __launch_bounds__(kSelThreads) void select_sliced(const float *__rest
     }
 }
 
+// ------------------------------------------------------------------------------------
+// Head-adaptive budgets (Appendix C, AdaKV paragraph): the layer's budget is spread over the
+// KV heads by ranking all (head, token) scores of a sequence together, after each head's own
+// top n_safe tokens (the safeguard) have been put beyond competition.  Done with the
+// selection above on a sequence's heads laid end to end, over order-preserving keys:
+//   adaptive_keys   key of every live token (>= 1), 0 for positions beyond the true length
+//   adaptive_mark   0xffffffff for every head's n_safe best (found by the per-head select)
+//   select          top Hkv * budget of the Hkv * N keys: ascending flat positions
+//   adaptive_split  flat positions -> per-head index lists and counts
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void adaptive_keys(const float *__restrict__ scores, int N, int Hkv, int ragged,
+                                                     SeqLens lens, size_t total, uint32_t *__restrict__ keys) {
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total) return;
+    const int p = (int)(t % N);
+    const int b = (int)(t / ((size_t)N * Hkv));
+    const uint32_t key = order_key(scores[t]);
+    keys[t] = p < seq_len_of(lens, ragged, b, N) ? (key < 1u ? 1u : key) : 0u;
+}
+
+__global__ __launch_bounds__(256) void adaptive_mark(const int32_t *__restrict__ safe_idx, int N, int n_safe,
+                                                     size_t total, uint32_t *__restrict__ keys) {
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;       // (bg, j)
+    if (t >= total) return;
+    const size_t bg = t / n_safe;
+    const int p = safe_idx[t];
+    if (p >= 0 && p < N) keys[bg * N + p] = 0xffffffffu;
+}
+
+// One block per (head, sequence): the head's share of the ascending flat list is the run of
+// positions in [g N, (g+1) N); its ends are found by bisection.
+__global__ __launch_bounds__(256) void adaptive_split(const int32_t *__restrict__ flat_idx, int N, int total_budget,
+                                                      int cap, int32_t *__restrict__ keep_idx,
+                                                      int32_t *__restrict__ counts) {
+    const int g = blockIdx.x, b = blockIdx.y, Hkv = gridDim.x;
+    const int32_t *flat = flat_idx + (size_t)b * total_budget;
+    auto lower_bound = [&](int value) {
+        int lo = 0, hi = total_budget;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (flat[mid] < value) lo = mid + 1; else hi = mid;
+        }
+        return lo;
+    };
+    const int begin = lower_bound(g * N), end = lower_bound((g + 1) * N);
+    const int count = min(end - begin, cap);
+    int32_t *out = keep_idx + ((size_t)b * Hkv + g) * cap;
+    for (int j = threadIdx.x; j < cap; j += 256) out[j] = j < count ? flat[begin + j] - g * N : -1;
+    if (threadIdx.x == 0) counts[(size_t)b * Hkv + g] = count;
+}
+
 }  // namespace
+
+static size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+
+size_t select_adaptive_workspace_bytes(int B, int Hkv, int N, int budget, int n_safe) {
+    const size_t BH = (size_t)B * Hkv;
+    size_t bytes = up256(BH * (size_t)(n_safe > 0 ? n_safe : 1) * sizeof(int32_t));     // safeguard indices
+    bytes += up256(BH * N * sizeof(uint32_t));                                           // keys
+    bytes += up256((size_t)B * Hkv * budget * sizeof(int32_t));                          // flat positions
+    if (select_prefers_slices(B, 1, Hkv * N)) bytes += select_workspace_bytes(B, 1, Hkv * N);
+    if (select_prefers_slices(B, Hkv, N)) bytes += select_workspace_bytes(B, Hkv, N);
+    return bytes;
+}
+
+hipError_t launch_select_adaptive(const float *scores, int budget, int n_safe, int cap, int32_t *keep_idx,
+                                  int32_t *counts, int B, int Hkv, int N, int ragged, const SeqLens &lens,
+                                  void *workspace, hipStream_t stream) {
+    const size_t BH = (size_t)B * Hkv;
+    char *base = (char *)workspace;
+    int32_t *safe_idx = (int32_t *)base;   base += up256(BH * (size_t)(n_safe > 0 ? n_safe : 1) * sizeof(int32_t));
+    uint32_t *keys = (uint32_t *)base;     base += up256(BH * N * sizeof(uint32_t));
+    int32_t *flat_idx = (int32_t *)base;   base += up256((size_t)B * Hkv * budget * sizeof(int32_t));
+    void *ws_flat = nullptr, *ws_head = nullptr;
+    size_t ws_flat_bytes = 0, ws_head_bytes = 0;
+    if (select_prefers_slices(B, 1, Hkv * N)) { ws_flat = base; ws_flat_bytes = select_workspace_bytes(B, 1, Hkv * N); base += ws_flat_bytes; }
+    if (select_prefers_slices(B, Hkv, N)) { ws_head = base; ws_head_bytes = select_workspace_bytes(B, Hkv, N); }
+    hipError_t e;
+    const size_t total = BH * N;
+    adaptive_keys<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(scores, N, Hkv, ragged, lens, total, keys);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (n_safe > 0) {
+        e = launch_select(scores, n_safe, safe_idx, B, Hkv, N, ragged, lens, 0, 0, 0, ws_head, ws_head_bytes, stream, 0);
+        if (e != hipSuccess) return e;
+        const size_t marks = BH * n_safe;
+        adaptive_mark<<<dim3((unsigned)((marks + 255) / 256)), dim3(256), 0, stream>>>(safe_idx, N, n_safe, marks, keys);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
+    SeqLens none;
+    std::memset(&none, 0, sizeof(none));
+    e = launch_select((const float *)keys, Hkv * budget, flat_idx, B, 1, Hkv * N, 0, none, 0, 0, 0, ws_flat, ws_flat_bytes,
+                      stream, 1);
+    if (e != hipSuccess) return e;
+    adaptive_split<<<dim3(Hkv, B), dim3(256), 0, stream>>>(flat_idx, N, Hkv * budget, cap, keep_idx, counts);
+    return hipGetLastError();
+}
 
 size_t select_workspace_bytes(int B, int Hkv, int N) {
     const size_t BH = (size_t)B * Hkv;
@@ -416,7 +518,7 @@ bool select_prefers_slices(int B, int Hkv, int N) {
 }
 
 hipError_t launch_select_sliced(const float *scores, int budget, int32_t *keep_idx, int B, int Hkv, int N, int ragged,
-                                const SeqLens &lens, int first, int tail, int radius, void *workspace,
+                                const SeqLens &lens, int first, int tail, int radius, int keys_in, void *workspace,
                                 hipStream_t stream) {
     const size_t BH = (size_t)B * Hkv;
     const int n_slices = (N + kSliceTok - 1) / kSliceTok;
@@ -427,7 +529,7 @@ hipError_t launch_select_sliced(const float *scores, int budget, int32_t *keep_i
     SliceState *state = (SliceState *)base;         base += up(4 * BH * sizeof(SliceState));
     int *counts = (int *)base;
     const dim3 grid(n_slices, (unsigned)BH), block(kSelThreads);
-#define OBC_SLICED_ARGS scores, N, budget, Hkv, ragged, lens, first, tail, radius, n_slices, hist_a, hist_b, state, counts, keep_idx
+#define OBC_SLICED_ARGS scores, N, budget, Hkv, ragged, lens, first, tail, radius, keys_in, n_slices, hist_a, hist_b, state, counts, keep_idx
     select_sliced<0><<<grid, block, 0, stream>>>(OBC_SLICED_ARGS);
     select_sliced<1><<<grid, block, 0, stream>>>(OBC_SLICED_ARGS);
     select_sliced<2><<<grid, block, 0, stream>>>(OBC_SLICED_ARGS);
@@ -439,17 +541,17 @@ hipError_t launch_select_sliced(const float *scores, int budget, int32_t *keep_i
 
 hipError_t launch_select(const float *scores, int budget, int32_t *keep_idx, int B, int Hkv, int N, int ragged,
                          const SeqLens &lens, int first, int tail, int radius, void *workspace,
-                         size_t workspace_bytes, hipStream_t stream) {
+                         size_t workspace_bytes, hipStream_t stream, int keys_in) {
     if (workspace && select_prefers_slices(B, Hkv, N) && workspace_bytes >= select_workspace_bytes(B, Hkv, N))
-        return launch_select_sliced(scores, budget, keep_idx, B, Hkv, N, ragged, lens, first, tail, radius, workspace,
-                                    stream);
+        return launch_select_sliced(scores, budget, keep_idx, B, Hkv, N, ragged, lens, first, tail, radius, keys_in,
+                                    workspace, stream);
     const dim3 grid(B * Hkv), block(kSelThreads);
     if (N <= 8 * kChunk)
-        select_topk<8, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, radius, keep_idx);
+        select_topk<8, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, radius, keys_in, keep_idx);
     else if (N <= 16 * kChunk)
-        select_topk<16, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, radius, keep_idx);
+        select_topk<16, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, radius, keys_in, keep_idx);
     else
-        select_topk<8, false><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, radius, keep_idx);
+        select_topk<8, false><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, radius, keys_in, keep_idx);
     return hipGetLastError();
 }
 

@@ -97,6 +97,15 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     assert pl(fake, 4, 0, 0, 0, 0, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EINVAL
     assert pl(fake, 4, 0, 0, 0, 17, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EUNSUPPORTED
     assert pl(fake, 17, 0, 0, 0, 5, fake, 1, 1, 16, None, None, 0, None) == obc.OBC_EINVAL
+    ad = lib.obc_select_adaptive           # (scores, budget, n_safe, keep, counts, cap, B, Hkv, N, lens, ws, ws_bytes, stream)
+    assert ad(fake, 4, 5, fake, fake, 16, 1, 2, 16, None, fake, 1 << 30, None) == obc.OBC_EINVAL     # n_safe > budget
+    assert ad(fake, 4, 1, fake, fake, 6, 1, 2, 16, None, fake, 1 << 30, None) == obc.OBC_EINVAL      # cap < 2*4 - 1
+    assert ad(fake, 4, 1, fake, None, 7, 1, 2, 16, None, fake, 1 << 30, None) == obc.OBC_EINVAL
+    assert ad(fake, 4, 1, fake, fake, 7, 1, 2, 16, None, None, 0, None) == obc.OBC_EWORKSPACE
+    assert ad(fake, 4, 1, fake, fake, 7, 1, 2, 16, None, fake, 64, None) == obc.OBC_EWORKSPACE
+    need = ctypes.c_size_t(0)
+    assert lib.obc_select_adaptive_workspace_bytes(4, 8, 32768, 2048, 409, ctypes.byref(need)) == obc.OBC_OK
+    assert need.value % 256 == 0 and need.value > 4 * 8 * 32768 * 4
     cs = lib.obc_compact_scores            # (scores, keep, out, B, Hkv, N, budget, N_out, stream)
     assert cs(fake, None, fake, 1, 1, 16, 4, 8, None) == obc.OBC_EINVAL
     assert cs(fake, fake, fake, 1, 1, 16, 4, 3, None) == obc.OBC_EINVAL               # N_out < budget

@@ -353,3 +353,41 @@ def test_select_on_scores_that_start_off_a_16_byte_boundary():
             assert view.data_ptr() % 16 != 0
             keep = obc.obc_select(view, budget).cpu().numpy()
             np.testing.assert_array_equal(keep, oracle.select(s, budget))
+
+
+def test_select_adaptive_matches_oracle_and_compacts_ragged_lists():
+    """Head-adaptive budgets (global ranking across the KV heads with a per-head safeguard): counts and index lists
+    bit-exact against the oracle; obc_compact turns the -1 padding into zero rows."""
+    dev = torch.device("cuda")
+    rng = np.random.default_rng(11)
+    skew = rng.random((2, 4, 3000)).astype(np.float32) ** 4
+    skew[:, 2] *= 20.0                                                     # one head attracts the budget
+    ties = np.floor(rng.random((3, 3, 700)) * 4).astype(np.float32)
+    long_heads = rng.random((1, 8, 32768)).astype(np.float32) ** 8         # the flattened row takes the sliced path
+    nanny = rng.standard_normal((1, 2, 500)).astype(np.float32); nanny[0, :, ::7] = np.nan
+    cases = [
+        (skew, 300, 60, None),
+        (skew, 300, 0, [3000, 1234]),
+        (skew, 300, 300, [3000, 1234]),                                    # full safeguard == per-head select
+        (ties, 100, 20, [700, 100, 333]),
+        (long_heads, 2048, 409, None),
+        (nanny, 200, 40, None),
+        (ties[:, :1], 50, 10, None),                                       # a single KV head
+    ]
+    for s, budget, n_safe, lens in cases:
+        st = torch.from_numpy(s).to(dev)
+        keep, counts = obc.obc_select_adaptive(st, budget, n_safe, seq_lens=lens)
+        want_keep, want_counts = oracle.select_adaptive(s, budget, n_safe, keep.shape[-1], lens)
+        np.testing.assert_array_equal(counts.cpu().numpy(), want_counts)
+        np.testing.assert_array_equal(keep.cpu().numpy(), want_keep)
+    # ragged lists through the gather: padded entries give zero rows
+    s, budget, n_safe, lens = cases[0]
+    g = torch.Generator().manual_seed(5)
+    k = torch.randn(2, 4, 3000, 128, generator=g).to(torch.bfloat16); v = torch.randn(2, 4, 3000, 128, generator=g).to(torch.bfloat16)
+    keep, counts = obc.obc_select_adaptive(torch.from_numpy(s).to(dev), budget, n_safe)
+    ko, vo = obc.obc_compact(k.to(dev), v.to(dev), keep)
+    kref, vref = oracle.compact(k.view(torch.int16).numpy(), v.view(torch.int16).numpy(), keep.cpu().numpy())
+    np.testing.assert_array_equal(ko.view(torch.int16).cpu().numpy(), kref)
+    np.testing.assert_array_equal(vo.view(torch.int16).cpu().numpy(), vref)
+    c = int(counts[0, 0])
+    assert c < keep.shape[-1] and torch.all(ko[0, 0, c:] == 0)

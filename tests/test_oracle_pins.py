@@ -490,3 +490,80 @@ def test_vatp_is_attention_score_times_l1_norm_and_ties_to_the_value_score():
     # padded rows may hold NaN
     v3 = v.copy(); v3[1, :, 33:] = np.nan; k3 = k.copy(); k3[1, :, 33:] = np.nan
     np.testing.assert_array_equal(oracle.vatp_score(q, k3, v3, seq_lens=lens), sp)
+
+
+# ---- head-adaptive selection (Appendix C, AdaKV paragraph: global ranking across heads, safeguard) ----
+
+def _split_flat(flat_sorted, Hkv, N, cap):
+    keep = np.full((Hkv, cap), -1, dtype=np.int32)
+    counts = np.zeros(Hkv, dtype=np.int32)
+    for f in flat_sorted:
+        g, p = divmod(int(f), N)
+        keep[g, counts[g]] = p
+        counts[g] += 1
+    return keep, counts
+
+
+def test_select_adaptive_without_safeguard_is_a_global_topk():
+    """Distinct scores, n_safe = 0: library top-k over the concatenated heads of each sequence."""
+    g = torch.Generator().manual_seed(88)
+    B, Hkv, N, budget = 2, 4, 150, 30
+    S = torch.rand(B, Hkv, N, generator=g)
+    S[:, 1] *= 3.0                                           # one head attracts most of the budget
+    cap = oracle.adaptive_cap(Hkv, budget, 0, N)
+    keep, counts = oracle.select_adaptive(S.numpy(), budget, 0, cap)
+    for b in range(B):
+        flat = torch.topk(S[b].reshape(-1), Hkv * budget).indices.sort().values.numpy()
+        want_keep, want_counts = _split_flat(flat, Hkv, N, cap)
+        np.testing.assert_array_equal(keep[b], want_keep)
+        np.testing.assert_array_equal(counts[b], want_counts)
+    assert counts[:, 1].min() > budget                       # the budget really moved between heads
+
+
+def test_select_adaptive_full_safeguard_is_the_per_head_select_and_invariants():
+    rng = np.random.default_rng(89)
+    B, Hkv, N, budget = 3, 3, 120, 20
+    s = np.floor(rng.random((B, Hkv, N)) * 7).astype(np.float32)         # ties everywhere
+    lens = [120, 45, 77]
+    keep, counts = oracle.select_adaptive(s, budget, budget, budget, lens)
+    np.testing.assert_array_equal(keep, oracle.select(s, budget, lens))
+    assert np.all(counts == budget)
+    n_safe = 4                                                            # floor(0.2 * budget)
+    cap = oracle.adaptive_cap(Hkv, budget, n_safe, max(lens))
+    keep, counts = oracle.select_adaptive(s, budget, n_safe, cap, lens)
+    safe = oracle.select(s, n_safe, lens)
+    for b in range(B):
+        L = lens[b]
+        assert counts[b].sum() == Hkv * budget and counts[b].min() >= n_safe
+        kept = np.zeros((Hkv, N), dtype=bool)
+        for h in range(Hkv):
+            row = keep[b, h]
+            c = counts[b, h]
+            assert np.all(np.diff(row[:c]) > 0) and np.all(row[c:] == -1) and row[:c].max() < L
+            kept[h, row[:c]] = True
+            assert kept[h, safe[b, h]].all()                              # the safeguard set is inside
+        # global threshold: no dropped live non-safeguard token beats a kept non-safeguard one, ties to lower (head, index)
+        issafe = np.zeros((Hkv, N), dtype=bool)
+        for h in range(Hkv):
+            issafe[h, safe[b, h]] = True
+        live = np.zeros((Hkv, N), dtype=bool); live[:, :L] = True
+        order = [(-float(s[b, h, p]), h, p) for h in range(Hkv) for p in range(L) if not issafe[h, p]]
+        order.sort()
+        want = set((h, p) for _, h, p in order[:Hkv * (budget - n_safe)])
+        got = set(zip(*np.nonzero(kept & ~issafe & live)))
+        assert got == want
+    with pytest.raises(ValueError):
+        oracle.select_adaptive(s, budget, budget + 1, cap, lens)
+    with pytest.raises(ValueError):
+        oracle.select_adaptive(s, budget, 0, 10, lens)                    # cap too small for the worst case
+
+
+def test_compact_pads_negative_indices_with_zero_rows():
+    rng = np.random.default_rng(91)
+    k = rng.integers(1, 2 ** 16, (1, 2, 9, 8)).astype(np.uint16)
+    v = rng.integers(1, 2 ** 16, (1, 2, 9, 8)).astype(np.uint16)
+    idx = np.array([[[0, 3, 8, -1], [2, -1, -1, -1]]], dtype=np.int32)
+    ko, vo = oracle.compact(k, v, idx)
+    np.testing.assert_array_equal(ko[0, 0, :3], k[0, 0, [0, 3, 8]])
+    np.testing.assert_array_equal(vo[0, 1, :1], v[0, 1, [2]])
+    assert np.all(ko[0, 0, 3:] == 0) and np.all(ko[0, 1, 1:] == 0) and np.all(vo[0, 1, 1:] == 0)
