@@ -222,6 +222,27 @@ int obc_compact(const void *k, const void *v, const int32_t *keep_idx,
                 int B, int Hkv, int N, int budget, int d, int dtype, void *hip_stream);
 
 /*
+ * Compaction where the cache lies (the specialised eviction kernel Appendix D asks for in
+ * place of gather + concatenate; Section 4.2, closing remark: an eviction at every decode
+ * step):
+ *   k[b,g,j,:] = k[b,g,keep_idx[b,g,j],:]  for j < budget, the same for v, and, when
+ *   `scores` is not NULL, scores[b,g,j] = scores[b,g,keep_idx[b,g,j]] for j < budget and
+ *   scores[b,g,j] = 0 for budget <= j < N (slots of tokens still to come).
+ *   k, v      [B, Hkv, N, d] of `dtype`, updated in place; rows budget..N-1 keep their old
+ *             (now stale) contents.
+ *   scores    [B, Hkv, N] fp32 or NULL.
+ *   keep_idx  [B, Hkv, budget] int32, per head strictly ascending as every obc_select*
+ *             call returns it (so keep_idx[j] >= j), optionally followed by -1 entries,
+ *             which give all-zero rows and zero scores.  Device data, not checked: entries
+ *             >= N are clamped to N-1; for a list that is not ascending the call stays
+ *             inside the buffers but the result is unspecified.
+ * Rows that already sit in their place (keep_idx[j] == j) are not rewritten.
+ * d * element size must be a multiple of 16 bytes; B * Hkv <= 65535.
+ */
+int obc_compact_inplace(void *k, void *v, float *scores, const int32_t *keep_idx,
+                        int B, int Hkv, int N, int budget, int d, int dtype, void *hip_stream);
+
+/*
  * Running scores follow their tokens through an eviction (Section 4.2, closing remark, and
  * Appendix C, decoding setup: scores accumulate over time and an eviction is made at every
  * step, so a kept token keeps its accumulated score):

@@ -72,6 +72,9 @@ def load_library():
     lib.obc_compact.restype = c_int
     lib.obc_compact.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int,
                                 c_int, c_void_p]
+    lib.obc_compact_inplace.restype = c_int
+    lib.obc_compact_inplace.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int,
+                                        c_void_p]
     lib.obc_compact_scores.restype = c_int
     lib.obc_compact_scores.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p]
     lib.obc_probe_read_bandwidth.restype = c_int
@@ -293,6 +296,28 @@ def obc_compact(k: torch.Tensor, v: torch.Tensor, keep_idx: torch.Tensor, k_out=
     if rc != OBC_OK:
         raise ObcError(rc, "obc_compact")
     return k_out, v_out
+
+
+def obc_compact_inplace(k: torch.Tensor, v: torch.Tensor, keep_idx: torch.Tensor,
+                        scores: Optional[torch.Tensor] = None) -> None:
+    """Moves rows keep_idx[b,g,j] of k, v (and entries of scores, whose tail is zeroed) to position j, in place."""
+    _require_cuda(k, v, keep_idx)
+    B, Hkv, N, d = k.shape
+    budget = keep_idx.shape[-1]
+    if keep_idx.dtype != torch.int32 or keep_idx.shape[:2] != (B, Hkv) or v.shape != k.shape:
+        raise ValueError("keep_idx must be [B,Hkv,budget] int32 matching k, v")
+    if not (k.is_contiguous() and v.is_contiguous() and keep_idx.is_contiguous()):
+        raise ValueError("k, v and keep_idx must be contiguous")
+    sp = None
+    if scores is not None:
+        _require_cuda(scores)
+        if tuple(scores.shape) != (B, Hkv, N) or scores.dtype != torch.float32 or not scores.is_contiguous():
+            raise ValueError("scores must be a contiguous [B,Hkv,N] float32 tensor")
+        sp = scores.data_ptr()
+    rc = load_library().obc_compact_inplace(k.data_ptr(), v.data_ptr(), sp, keep_idx.data_ptr(), B, Hkv, N, budget, d,
+                                            _dtype_code(k), _stream_ptr(k))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_compact_inplace")
 
 
 def obc_compact_scores(scores: torch.Tensor, keep_idx: torch.Tensor, n_out: Optional[int] = None,

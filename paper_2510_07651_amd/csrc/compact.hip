@@ -44,6 +44,90 @@ __global__ __launch_bounds__(256) void gather_scores(const float *__restrict__ i
     out[t] = x;
 }
 
+// In-place compaction of one KV head's rows: row j takes the place of row keep_idx[j] >= j.
+// A workgroup owns a 64-byte column slice of all rows of one head of K (blockIdx.y == 0) or V
+// (1) and walks the index list in chunks of kMoveChunk rows: every thread loads its pieces of
+// its source rows, the workgroup meets at a barrier, then every thread stores.  Sources of a
+// chunk lie at or above the chunk's first row, so they are untouched by the stores of earlier
+// chunks and are all read before this chunk's stores; later chunks read above everything
+// stored so far.  The walk starts near the first row that moves at all (the list is ascending,
+// so the rows before it are a prefix that stays where it is).
+// blockIdx.y == 2 moves the running scores the same way and clears their tail.
+constexpr int kMoveThreads = 1024;
+constexpr int kMoveRows = 8;                                 // rows per thread and chunk
+constexpr int kMoveChunk = kMoveThreads / 4 * kMoveRows;     // rows per chunk (four 16-byte pieces per row slice)
+
+__global__ __launch_bounds__(kMoveThreads) void move_rows_in_place(uint4 *__restrict__ k, uint4 *__restrict__ v,
+                                                                   float *__restrict__ scores,
+                                                                   const int32_t *__restrict__ keep_idx, int N,
+                                                                   int budget, int row_vec) {
+    __shared__ int first_probe;
+    const size_t bg = blockIdx.z;
+    const int32_t *keep = keep_idx + bg * budget;
+    if (blockIdx.y == 2 && blockIdx.x != 0) return;
+
+    // Probe kMoveThreads evenly spaced positions; everything up to the last probe before the
+    // first one that moves is known to stay.
+    const int stride = (budget + kMoveThreads - 1) / kMoveThreads;
+    if (threadIdx.x == 0) first_probe = kMoveThreads;
+    __syncthreads();
+    const long long pos = (long long)threadIdx.x * stride;
+    if (pos >= budget || keep[pos] != (int)pos) atomicMin(&first_probe, (int)threadIdx.x);
+    __syncthreads();
+    const int begin = first_probe == 0 ? 0 : (first_probe - 1) * stride;
+
+    if (blockIdx.y == 2) {
+        float *s = scores + bg * N;
+        for (int j0 = begin; j0 < budget; j0 += kMoveThreads * kMoveRows) {
+            float x[kMoveRows];
+            int p[kMoveRows];
+#pragma unroll
+            for (int u = 0; u < kMoveRows; ++u) {
+                const int j = j0 + u * kMoveThreads + threadIdx.x;
+                x[u] = 0.f;
+                p[u] = -1;
+                if (j < budget) {
+                    p[u] = keep[j];
+                    p[u] = p[u] >= N ? N - 1 : p[u];
+                    if (p[u] >= 0) x[u] = s[p[u]];
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kMoveRows; ++u) {
+                const int j = j0 + u * kMoveThreads + threadIdx.x;
+                if (j < budget && p[u] != j) s[j] = x[u];
+            }
+        }
+        for (int j = budget + threadIdx.x; j < N; j += kMoveThreads) s[j] = 0.f;
+        return;
+    }
+    uint4 *rows = (blockIdx.y == 0 ? k : v) + bg * N * row_vec;
+    const int c = blockIdx.x * 4 + (threadIdx.x & 3);
+    const int r = threadIdx.x >> 2;
+    for (int j0 = begin; j0 < budget; j0 += kMoveChunk) {
+        uint4 x[kMoveRows];
+        int p[kMoveRows];
+#pragma unroll
+        for (int u = 0; u < kMoveRows; ++u) {
+            const int j = j0 + u * (kMoveThreads / 4) + r;
+            x[u] = make_uint4(0, 0, 0, 0);
+            p[u] = -1;
+            if (j < budget && c < row_vec) {
+                p[u] = keep[j];
+                p[u] = p[u] >= N ? N - 1 : p[u];
+                if (p[u] >= 0) x[u] = rows[(size_t)p[u] * row_vec + c];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < kMoveRows; ++u) {
+            const int j = j0 + u * (kMoveThreads / 4) + r;
+            if (j < budget && c < row_vec && p[u] != j) rows[(size_t)j * row_vec + c] = x[u];
+        }
+    }
+}
+
 // Measurement hook: reads `n_vec` 16-byte words once with 128-bit loads and folds them
 // into one word per thread (so the loads cannot be dropped).  Its duration gives the box's
 // own streaming-read ceiling, the practical denominator next to the nominal HBM peak.
@@ -70,6 +154,14 @@ hipError_t launch_gather_scores(const float *in, const int32_t *keep_idx, float 
 
 hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int blocks, hipStream_t stream) {
     stream_read<<<dim3(blocks), dim3(256), 0, stream>>>((const uint4 *)src, bytes / 16, sink);
+    return hipGetLastError();
+}
+
+hipError_t launch_compact_in_place(void *k, void *v, float *scores, const int32_t *keep_idx, int B, int Hkv, int N,
+                                   int budget, int row_bytes, hipStream_t stream) {
+    const int row_vec = row_bytes / 16;
+    const dim3 grid((unsigned)((row_vec + 3) / 4), scores ? 3 : 2, (unsigned)(B * Hkv));
+    move_rows_in_place<<<grid, dim3(kMoveThreads), 0, stream>>>((uint4 *)k, (uint4 *)v, scores, keep_idx, N, budget, row_vec);
     return hipGetLastError();
 }
 

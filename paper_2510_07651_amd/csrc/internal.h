@@ -49,11 +49,27 @@ struct ScoreWorkspace {
     int split_len;     // tokens per split (multiple of 64)
     int range_len;     // tokens per workgroup in the second sweep (multiple of 64)
     int use_mfma;      // 1: matrix-core path, 0: plain path
+    // Decode path (one window row per query head): see score_decode.hip.
+    size_t dec_z;      // float [B*Hkv*N*dec_rows]  scaled logits, token-major
+    size_t dec_part;   // float [B*Hkv*dec_splits*dec_rows*(d+4)]  per-range partial records
+    size_t dec_final;  // float [B*Hkv*dec_rows*(2d+4)]  merged row records
+    int use_decode;    // 1: decode path (takes precedence over the other two)
+    int dec_rows;      // query heads per KV head, padded to 1, 2, 4 or 8
+    int dec_range;     // tokens per workgroup (multiple of 32)
+    int dec_splits;    // ranges per KV head
+    int dec_merge_inline;  // 1: the scoring kernel merges the ranges itself
 };
+
+constexpr int kDecodeMaxGroup = 8;   // query heads per KV head the decode path is built for
 
 int plan_score_workspace(int B, int N, int W, int Hq, int Hkv, int d, int dtype, int variant, ScoreWorkspace *ws);
 // Adds the matrix-core path's buffers to the plan, advancing *off (bytes).
 void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWorkspace *ws, size_t *off);
+
+// Decode path: whether it covers the shape, its buffers (advancing *off), its launcher.
+bool decode_path_covers(int N, int W, int Hq, int Hkv, int d, int dtype);
+void decode_plan(int B, int N, int Hq, int Hkv, int d, ScoreWorkspace *ws, size_t *off);
+hipError_t launch_score_decode(const ScoreArgs &a, const ScoreWorkspace &ws, char *ws_base, hipStream_t stream);
 
 // Launchers.  Each enqueues on `stream` and returns hipSuccess or the launch error.
 hipError_t launch_score_plain(const ScoreArgs &a, const ScoreWorkspace &ws, char *ws_base, hipStream_t stream);
@@ -69,6 +85,8 @@ size_t select_workspace_bytes(int B, int Hkv, int N);
 bool select_prefers_slices(int B, int Hkv, int N);
 hipError_t launch_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_out, void *v_out, int B,
                           int Hkv, int N, int budget, int row_bytes, hipStream_t stream);
+hipError_t launch_compact_in_place(void *k, void *v, float *scores, const int32_t *keep_idx, int B, int Hkv, int N,
+                                   int budget, int row_bytes, hipStream_t stream);
 hipError_t launch_gather_scores(const float *in, const int32_t *keep_idx, float *out, int BH, int N, int budget,
                                  int n_out, hipStream_t stream);
 hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int blocks, hipStream_t stream);

@@ -21,9 +21,11 @@ static int check_score_shape(int B, int N, int W, int Hq, int Hkv, int d, int dt
     return OBC_OK;
 }
 
-static bool force_plain_path() {
-    const char *e = std::getenv("OBC_SCORE_PATH");   // "plain" routes bf16 d=128 through the vector-ALU kernels too
-    return e && std::strcmp(e, "plain") == 0;
+// OBC_SCORE_PATH pins the scoring path for comparisons: "plain" routes everything through the
+// general vector-ALU kernels, "mfma" keeps one-row windows on the matrix-core path.
+static bool score_path_is(const char *name) {
+    const char *e = std::getenv("OBC_SCORE_PATH");
+    return e && std::strcmp(e, name) == 0;
 }
 
 int plan_score_workspace(int B, int N, int W, int Hq, int Hkv, int d, int dtype, int variant, ScoreWorkspace *ws) {
@@ -32,7 +34,9 @@ int plan_score_workspace(int B, int N, int W, int Hq, int Hkv, int d, int dtype,
     std::memset(ws, 0, sizeof(*ws));
     const int G = Hq / Hkv;
     const size_t rows = (size_t)B * Hq * W;
-    ws->use_mfma = (dtype == OBC_BF16 && d == 128 && !force_plain_path()) ? 1 : 0;
+    const bool pinned = score_path_is("plain") || score_path_is("mfma");
+    ws->use_decode = (decode_path_covers(N, W, Hq, Hkv, d, dtype) && !pinned) ? 1 : 0;
+    ws->use_mfma = (!ws->use_decode && dtype == OBC_BF16 && d == 128 && !score_path_is("plain")) ? 1 : 0;
     ws->m_pad = (G * W + 31) / 32 * 32;
     size_t off = 0;
     ws->row_max = off;  off = align_up(off + rows * sizeof(float), 256);
@@ -41,7 +45,9 @@ int plan_score_workspace(int B, int N, int W, int Hq, int Hkv, int d, int dtype,
     ws->out_rest_f32 = off;  off = align_up(off + rows * d * sizeof(float), 256);
     ws->rest_frac = off;  off = align_up(off + rows * sizeof(float), 256);
     ws->top_token = off;  off = align_up(off + rows * sizeof(int32_t), 256);
-    if (ws->use_mfma) {
+    if (ws->use_decode) {
+        decode_plan(B, N, Hq, Hkv, d, ws, &off);
+    } else if (ws->use_mfma) {
         mfma_plan(B, N, W, Hq, Hkv, d, variant, ws, &off);
     }
     ws->total = align_up(off, 256);
@@ -67,7 +73,7 @@ using namespace obc;
 
 extern "C" {
 
-int obc_version(void) { return 101; }
+int obc_version(void) { return 102; }
 
 const char *obc_status_string(int status) {
     switch (status) {
@@ -135,8 +141,9 @@ static int score_impl(const void *q, const void *k, const void *v, int N, int W,
     hipStream_t stream = (hipStream_t)hip_stream;
     a.stage_mask = stage_mask;
     a.accumulate = accumulate;
-    const hipError_t e = ws.use_mfma ? launch_score_mfma(a, ws, (char *)workspace, stream)
-                                     : launch_score_plain(a, ws, (char *)workspace, stream);
+    const hipError_t e = ws.use_decode ? launch_score_decode(a, ws, (char *)workspace, stream)
+                         : ws.use_mfma ? launch_score_mfma(a, ws, (char *)workspace, stream)
+                                       : launch_score_plain(a, ws, (char *)workspace, stream);
     return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
 }
 
@@ -234,6 +241,20 @@ int obc_compact(const void *k, const void *v, const int32_t *keep_idx, void *k_o
     if ((long long)B * Hkv * budget * (row_bytes / 16) > (1LL << 38)) return OBC_EUNSUPPORTED;
     const hipError_t e = launch_compact(k, v, keep_idx, k_out, v_out, B, Hkv, N, budget, (int)row_bytes,
                                         (hipStream_t)hip_stream);
+    return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
+}
+
+int obc_compact_inplace(void *k, void *v, float *scores, const int32_t *keep_idx, int B, int Hkv, int N, int budget,
+                        int d, int dtype, void *hip_stream) {
+    if (!k || !v || !keep_idx) return OBC_EINVAL;
+    if ((((uintptr_t)k | (uintptr_t)v) & 15) != 0 || ((uintptr_t)scores & 3) != 0) return OBC_EINVAL;
+    if (B < 1 || Hkv < 1 || N < 1 || budget < 1 || budget > N || d < 1) return OBC_EINVAL;
+    if (dtype != OBC_F32 && dtype != OBC_BF16) return OBC_EUNSUPPORTED;
+    const long long row_bytes = (long long)d * (dtype == OBC_F32 ? 4 : 2);
+    if (row_bytes % 16 != 0 || row_bytes > (1 << 20)) return OBC_EUNSUPPORTED;
+    if ((long long)B * Hkv > 65535 || (long long)N > (1LL << 30)) return OBC_EUNSUPPORTED;
+    const hipError_t e = launch_compact_in_place(k, v, scores, keep_idx, B, Hkv, N, budget, (int)row_bytes,
+                                                 (hipStream_t)hip_stream);
     return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
 }
 

@@ -119,6 +119,14 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     assert cp(fake, fake, fake, ctypes.c_void_p(4104), fake, 1, 1, 16, 4, 64, 0, None) == obc.OBC_EINVAL   # misaligned output
     assert cp(fake, fake, fake, fake, fake, 1, 1, 16, 4, 6, 1, None) == obc.OBC_EUNSUPPORTED   # 12-byte rows
     assert cp(fake, fake, fake, fake, fake, 1, 1, 16, 4, 64, 9, None) == obc.OBC_EUNSUPPORTED  # dtype
+    ip = lib.obc_compact_inplace           # (k, v, scores|NULL, keep, B, Hkv, N, budget, d, dtype, stream)
+    assert ip(fake, fake, None, None, 1, 1, 16, 4, 64, 0, None) == obc.OBC_EINVAL
+    assert ip(fake, None, None, fake, 1, 1, 16, 4, 64, 0, None) == obc.OBC_EINVAL
+    assert ip(fake, fake, None, fake, 1, 1, 16, 17, 64, 0, None) == obc.OBC_EINVAL            # budget > N
+    assert ip(fake, ctypes.c_void_p(4104), None, fake, 1, 1, 16, 4, 64, 0, None) == obc.OBC_EINVAL   # misaligned cache
+    assert ip(fake, fake, ctypes.c_void_p(4098), fake, 1, 1, 16, 4, 64, 0, None) == obc.OBC_EINVAL   # misaligned scores
+    assert ip(fake, fake, None, fake, 1, 1, 16, 4, 6, 1, None) == obc.OBC_EUNSUPPORTED       # 12-byte rows
+    assert ip(fake, fake, None, fake, 1, 1, 16, 4, 64, 7, None) == obc.OBC_EUNSUPPORTED      # dtype
 
 
 def test_bench_refuses_more_than_one_gpu():

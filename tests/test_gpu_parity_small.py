@@ -12,50 +12,11 @@ import oracle
 from paper_2510_07651_amd import binding as obc
 from paper_2510_07651_amd import synth
 
-from parity_util import (TOL, check_keep_idx_valid, check_selection_against_oracle_scores, oracle_scores,
-                         score_error, to_device)
+from parity_util import TOL, run_case as _run_case, score_error, to_device
 
 pytestmark = pytest.mark.gpu
 
 CASES = {w.name: w for w in synth.small_cases() + synth.paper_configs()[:2]}
-
-
-def _run_case(wl):
-    x = synth.make_inputs(wl)
-    dev = to_device(x)
-    lens = x["seq_lens"]
-    tol = TOL[wl.dtype]
-    ref = oracle_scores(x)
-    all3 = obc.obc_score(dev["q"], dev["k"], dev["v"], "all", seq_lens=lens)
-    torch.cuda.synchronize()
-    assert all3.shape == (3, wl.B, wl.Hkv, wl.N)
-    worst = {}
-    for vi, name in enumerate(synth.VARIANTS):
-        gpu = all3[vi].cpu().numpy()
-        assert np.isfinite(gpu).all() and (gpu >= 0).all(), name
-        worst[name], where = score_error(gpu, ref[vi], wl.budget, lens, tol)
-        assert worst[name] <= tol, "%s %s: err %.3g at %s" % (wl.name, name, worst[name], where)
-        # single-variant calls agree with the all-variant call (the value-only call skips the
-        # attention outputs, and with them the refinement of dominant rows, so bits may differ)
-        one = obc.obc_score(dev["q"], dev["k"], dev["v"], name, seq_lens=lens)
-        if name == "value":
-            torch.testing.assert_close(one, all3[vi], rtol=2e-5, atol=0.0)
-        else:
-            assert torch.equal(one, all3[vi]), name
-        # selection: bit-exact vs the oracle's select on the very same fp32 scores
-        keep = obc.obc_select(all3[vi].contiguous(), wl.budget, seq_lens=lens)
-        keep_np = keep.cpu().numpy()
-        check_keep_idx_valid(keep_np, wl.budget, lens, wl.N)
-        np.testing.assert_array_equal(keep_np, oracle.select(gpu, wl.budget, lens))
-        # and consistent with the oracle's own scores outside the tolerance band
-        check_selection_against_oracle_scores(keep_np, ref[vi], wl.budget, lens, tol)
-    # compaction: byte-exact gather
-    k_out, v_out = obc.obc_compact(dev["k"], dev["v"], keep)
-    as_bits = (lambda t: t.view(torch.int16)) if wl.dtype == "bf16" else (lambda t: t.view(torch.int32))
-    kref, vref = oracle.compact(as_bits(x["k"]).numpy(), as_bits(x["v"]).numpy(), keep_np)
-    np.testing.assert_array_equal(as_bits(k_out).cpu().numpy(), kref)
-    np.testing.assert_array_equal(as_bits(v_out).cpu().numpy(), vref)
-    return worst
 
 
 @pytest.mark.parametrize("name", list(CASES))
@@ -230,7 +191,8 @@ def test_accumulate_onto_zeros_equals_plain_call_with_several_row_chunks():
     assert torch.equal(run, plain + plain)
 
 
-def test_decode_eviction_loop_matches_oracle():
+@pytest.mark.parametrize("in_place", [False, True])
+def test_decode_eviction_loop_matches_oracle(in_place):
     """The decoding setup of Appendix C in miniature: every step appends a token, accumulates its scores, and once the
     cache is over budget evicts one token per head with sinks and a recent window protected.  The oracle runs the same
     loop in fp64; eviction decisions are taken on the same fp32 running scores on both sides and must be identical."""
@@ -260,11 +222,15 @@ def test_decode_eviction_loop_matches_oracle():
             keep = obc.obc_select_protected(run, hh, sinks, recent, 0, seq_lens=lens)
             keep_np = keep.cpu().numpy()
             np.testing.assert_array_equal(keep_np, oracle.select_protected(run.cpu().numpy(), hh, sinks, recent, 0, lens))
-            ko, vo = obc.obc_compact(k, v, keep)
-            new_run = obc.obc_compact_scores(run, keep, n_out=cap)
-            k = torch.zeros_like(k); v = torch.zeros_like(v)
-            k[:, :, :budget] = ko; v[:, :, :budget] = vo
-            run = new_run
+            if in_place:
+                obc.obc_compact_inplace(k, v, keep, scores=run)
+                k[:, :, budget:] = 0; v[:, :, budget:] = 0        # stale rows; cleared only to compare whole caches below
+            else:
+                ko, vo = obc.obc_compact(k, v, keep)
+                new_run = obc.obc_compact_scores(run, keep, n_out=cap)
+                k = torch.zeros_like(k); v = torch.zeros_like(v)
+                k[:, :, :budget] = ko; v[:, :, :budget] = vo
+                run = new_run
             idx = keep_np[..., None]
             k_new = np.zeros_like(k_ref); v_new = np.zeros_like(v_ref); r_new = np.zeros_like(run_ref)
             k_new[:, :, :budget] = np.take_along_axis(k_ref, idx, axis=2)
@@ -391,3 +357,53 @@ def test_select_adaptive_matches_oracle_and_compacts_ragged_lists():
     np.testing.assert_array_equal(vo.view(torch.int16).cpu().numpy(), vref)
     c = int(counts[0, 0])
     assert c < keep.shape[-1] and torch.all(ko[0, 0, c:] == 0)
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp32", 128), ("fp32", 20)])
+def test_compact_inplace_matches_oracle_gather(dtype, d):
+    """Appendix D's "specialised kernel for cache eviction": the in-place form must leave exactly what the oracle's
+    gather gives in rows [0, budget), leave the rows behind untouched, move the scores along and zero their tail."""
+    B, Hkv, N = 3, 2, 1000
+    g = torch.Generator().manual_seed(61)
+    dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    k = torch.randn(B, Hkv, N, d, generator=g).to(dt); v = torch.randn(B, Hkv, N, d, generator=g).to(dt)
+    s = torch.rand(B, Hkv, N, generator=g)
+    bits = (lambda t: t.view(torch.int16)) if dtype == "bf16" else (lambda t: t.view(torch.int32))
+    lists = {
+        "evict_one": lambda n: np.delete(np.arange(n), n // 3),
+        "evict_first": lambda n: np.arange(1, n),
+        "evict_last": lambda n: np.arange(n - 1),
+        "keep_everything": lambda n: np.arange(n),
+        "keep_tail": lambda n: np.arange(n - 130, n),
+        "random_third": lambda n: np.sort(np.random.default_rng(62).choice(n, n // 3, replace=False)),
+        "one_row": lambda n: np.array([n - 1]),
+    }
+    for name, make in lists.items():
+        base = make(N)
+        keep = np.stack([np.stack([base if (b + h) % 2 == 0 or name != "random_third" else
+                                   np.sort(np.random.default_rng(63 + b).choice(N, len(base), replace=False))
+                                   for h in range(Hkv)]) for b in range(B)]).astype(np.int32)
+        budget = keep.shape[-1]
+        kd, vd, sd = k.cuda(), v.cuda(), s.cuda()
+        obc.obc_compact_inplace(kd, vd, torch.from_numpy(keep).cuda(), scores=sd)
+        kref, vref = oracle.compact(bits(k).numpy(), bits(v).numpy(), keep)
+        np.testing.assert_array_equal(bits(kd).cpu().numpy()[:, :, :budget], kref, err_msg=name)
+        np.testing.assert_array_equal(bits(vd).cpu().numpy()[:, :, :budget], vref, err_msg=name)
+        np.testing.assert_array_equal(bits(kd).cpu().numpy()[:, :, budget:], bits(k).numpy()[:, :, budget:], err_msg=name)
+        np.testing.assert_array_equal(bits(vd).cpu().numpy()[:, :, budget:], bits(v).numpy()[:, :, budget:], err_msg=name)
+        np.testing.assert_array_equal(sd.cpu().numpy()[:, :, :budget], np.take_along_axis(s.numpy(), keep, axis=2))
+        assert np.all(sd.cpu().numpy()[:, :, budget:] == 0.0), name
+        # without scores the cache moves all the same
+        kd2, vd2 = k.cuda(), v.cuda()
+        obc.obc_compact_inplace(kd2, vd2, torch.from_numpy(keep).cuda())
+        assert torch.equal(bits(kd2), bits(kd)) and torch.equal(bits(vd2), bits(vd)), name
+    # a ragged list padded with -1 (what obc_select_adaptive returns) gives zero rows and zero scores
+    keep = np.full((B, Hkv, 40), -1, np.int32)
+    keep[:, :, :25] = np.arange(5, 30)
+    kd, vd, sd = k.cuda(), v.cuda(), s.cuda()
+    obc.obc_compact_inplace(kd, vd, torch.from_numpy(keep).cuda(), scores=sd)
+    kref, vref = oracle.compact(bits(k).numpy(), bits(v).numpy(), keep)
+    np.testing.assert_array_equal(bits(kd).cpu().numpy()[:, :, :40], kref)
+    np.testing.assert_array_equal(bits(vd).cpu().numpy()[:, :, :40], vref)
+    assert np.all(sd.cpu().numpy()[:, :, 25:] == 0.0)
+    np.testing.assert_array_equal(sd.cpu().numpy()[:, :, :25], s.numpy()[:, :, 5:30])
