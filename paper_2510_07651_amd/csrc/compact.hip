@@ -68,13 +68,16 @@ __global__ __launch_bounds__(kMoveThreads) void move_rows_in_place(uint4 *__rest
 
     // Probe kMoveThreads evenly spaced positions; everything up to the last probe before the
     // first one that moves is known to stay.
-    const int stride = (budget + kMoveThreads - 1) / kMoveThreads;
-    if (threadIdx.x == 0) first_probe = kMoveThreads;
-    __syncthreads();
-    const long long pos = (long long)threadIdx.x * stride;
-    if (pos >= budget || keep[pos] != (int)pos) atomicMin(&first_probe, (int)threadIdx.x);
-    __syncthreads();
-    const int begin = first_probe == 0 ? 0 : (first_probe - 1) * stride;
+    int begin = 0;
+    if (budget > kMoveChunk) {                      // (a list of one chunk is walked from its start: nothing to save)
+        const int stride = (budget + kMoveThreads - 1) / kMoveThreads;
+        if (threadIdx.x == 0) first_probe = kMoveThreads;
+        __syncthreads();
+        const long long pos = (long long)threadIdx.x * stride;
+        if (pos >= budget || keep[pos] != (int)pos) atomicMin(&first_probe, (int)threadIdx.x);
+        __syncthreads();
+        begin = first_probe == 0 ? 0 : (first_probe - 1) * stride;
+    }
 
     if (blockIdx.y == 2) {
         float *s = scores + bg * N;

@@ -67,7 +67,7 @@ int plan_score_workspace(int B, int N, int W, int Hq, int Hkv, int d, int dtype,
 void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWorkspace *ws, size_t *off);
 
 // Decode path: whether it covers the shape, its buffers (advancing *off), its launcher.
-bool decode_path_covers(int N, int W, int Hq, int Hkv, int d, int dtype);
+bool decode_path_covers(int B, int N, int W, int Hq, int Hkv, int d, int dtype, int variant, bool any_size);
 void decode_plan(int B, int N, int Hq, int Hkv, int d, ScoreWorkspace *ws, size_t *off);
 hipError_t launch_score_decode(const ScoreArgs &a, const ScoreWorkspace &ws, char *ws_base, hipStream_t stream);
 

@@ -22,7 +22,8 @@ static int check_score_shape(int B, int N, int W, int Hq, int Hkv, int d, int dt
 }
 
 // OBC_SCORE_PATH pins the scoring path for comparisons: "plain" routes everything through the
-// general vector-ALU kernels, "mfma" keeps one-row windows on the matrix-core path.
+// general vector-ALU kernels, "mfma" keeps one-row windows on the matrix-core path, "decode"
+// sends them to the decode kernels whatever the cache size.
 static bool score_path_is(const char *name) {
     const char *e = std::getenv("OBC_SCORE_PATH");
     return e && std::strcmp(e, name) == 0;
@@ -35,7 +36,7 @@ int plan_score_workspace(int B, int N, int W, int Hq, int Hkv, int d, int dtype,
     const int G = Hq / Hkv;
     const size_t rows = (size_t)B * Hq * W;
     const bool pinned = score_path_is("plain") || score_path_is("mfma");
-    ws->use_decode = (decode_path_covers(N, W, Hq, Hkv, d, dtype) && !pinned) ? 1 : 0;
+    ws->use_decode = (decode_path_covers(B, N, W, Hq, Hkv, d, dtype, variant, score_path_is("decode")) && !pinned) ? 1 : 0;
     ws->use_mfma = (!ws->use_decode && dtype == OBC_BF16 && d == 128 && !score_path_is("plain")) ? 1 : 0;
     ws->m_pad = (G * W + 31) / 32 * 32;
     size_t off = 0;

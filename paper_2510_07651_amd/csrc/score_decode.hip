@@ -638,9 +638,15 @@ int splits_for(int N, int d) { return (N + range_tokens(d) - 1) / range_tokens(d
 
 }  // namespace
 
-bool decode_path_covers(int N, int W, int Hq, int Hkv, int d, int dtype) {
+bool decode_path_covers(int B, int N, int W, int Hq, int Hkv, int d, int dtype, int variant, bool any_size) {
     if (dtype != OBC_BF16 || W != 1 || Hq / Hkv > kDecodeMaxGroup || (d != 64 && d != 128)) return false;
-    return splits_for(N, d) <= kMaxSplits;          // what one merging workgroup takes
+    if (splits_for(N, d) > kMaxSplits) return false;            // what one merging workgroup takes
+    // These kernels win while the call is bound by round trips.  On long caches the direct forms
+    // of the norms make them vector-ALU bound and the matrix-core path is faster (measured
+    // crossover on gfx950: about 1e5 head-tokens when o_i is needed, 2.6e5 when it is not).
+    const bool need_o = variant == OBC_KEY || variant == OBC_JOINT || variant == OBC_ALL;
+    const long long head_tokens = (long long)B * Hkv * N;
+    return any_size || d != 128 || head_tokens <= (need_o ? 98304 : 262144);   // (head_dim 64 has no matrix-core path)
 }
 
 void decode_plan(int B, int N, int Hq, int Hkv, int d, ScoreWorkspace *ws, size_t *off) {

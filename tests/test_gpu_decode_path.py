@@ -41,7 +41,8 @@ CASES = {w.name: w for w in [
 
 
 @pytest.mark.parametrize("name", list(CASES))
-def test_decode_scores_select_compact_match_oracle(name):
+def test_decode_scores_select_compact_match_oracle(name, monkeypatch):
+    monkeypatch.setenv("OBC_SCORE_PATH", "decode")      # whatever the size (long caches go to the matrix cores otherwise)
     worst = run_case(CASES[name])
     print(name, {k: "%.2e" % v for k, v in worst.items()})
 
@@ -55,7 +56,8 @@ def test_attention_mass_of_the_dominant_case():
 
 
 @pytest.mark.parametrize("name", ["d_llama_1025", "d_qwen_g7", "d_g2_ragged", "d_long_separate_merge", "d_mha_d64"])
-def test_decode_attention_only_and_vatp_match_oracle(name):
+def test_decode_attention_only_and_vatp_match_oracle(name, monkeypatch):
+    monkeypatch.setenv("OBC_SCORE_PATH", "decode")
     wl = CASES[name]
     x = synth.make_inputs(wl)
     dev = to_device(x)
@@ -69,7 +71,8 @@ def test_decode_attention_only_and_vatp_match_oracle(name):
 
 
 @pytest.mark.parametrize("name", ["d_llama_1025", "d_long_separate_merge"])
-def test_decode_accumulate_adds_and_leaves_padding_alone(name):
+def test_decode_accumulate_adds_and_leaves_padding_alone(name, monkeypatch):
+    monkeypatch.setenv("OBC_SCORE_PATH", "decode")
     wl = CASES[name]
     x = synth.make_inputs(wl)
     dev = to_device(x)
@@ -92,3 +95,8 @@ def test_matrix_core_path_still_serves_one_row_windows(monkeypatch):
     run_case(CASES["d_llama_1025"])
     run_case(CASES["d_one_key_takes_all"])
     run_case(CASES["d_one_key_takes_all_harder"])
+
+
+def test_long_caches_take_the_matrix_core_path_by_default():
+    """Past the measured crossover a one-row window goes to the matrix-core kernels; both routes meet the oracle."""
+    run_case(CASES["d_many_ranges"])

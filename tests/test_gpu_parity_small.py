@@ -359,11 +359,13 @@ def test_select_adaptive_matches_oracle_and_compacts_ragged_lists():
     assert c < keep.shape[-1] and torch.all(ko[0, 0, c:] == 0)
 
 
-@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("fp32", 128), ("fp32", 20)])
-def test_compact_inplace_matches_oracle_gather(dtype, d):
+@pytest.mark.parametrize("dtype,d,N", [("bf16", 128, 1000), ("bf16", 64, 1000), ("fp32", 128, 1000), ("fp32", 20, 1000),
+                                       ("bf16", 128, 9000)])
+def test_compact_inplace_matches_oracle_gather(dtype, d, N):
     """Appendix D's "specialised kernel for cache eviction": the in-place form must leave exactly what the oracle's
-    gather gives in rows [0, budget), leave the rows behind untouched, move the scores along and zero their tail."""
-    B, Hkv, N = 3, 2, 1000
+    gather gives in rows [0, budget), leave the rows behind untouched, move the scores along and zero their tail.
+    The longest case spans several chunks of the kernel's walk and its search for the first row that moves."""
+    B, Hkv = 3, 2
     g = torch.Generator().manual_seed(61)
     dt = torch.bfloat16 if dtype == "bf16" else torch.float32
     k = torch.randn(B, Hkv, N, d, generator=g).to(dt); v = torch.randn(B, Hkv, N, d, generator=g).to(dt)
@@ -376,6 +378,8 @@ def test_compact_inplace_matches_oracle_gather(dtype, d):
         "keep_everything": lambda n: np.arange(n),
         "keep_tail": lambda n: np.arange(n - 130, n),
         "random_third": lambda n: np.sort(np.random.default_rng(62).choice(n, n // 3, replace=False)),
+        "random_most": lambda n: np.sort(np.random.default_rng(64).choice(n, n - n // 10, replace=False)),
+        "evict_late": lambda n: np.delete(np.arange(n), n - 7),
         "one_row": lambda n: np.array([n - 1]),
     }
     for name, make in lists.items():
