@@ -34,7 +34,62 @@ def parse():
     ap.add_argument("--variant", default="joint")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = the whole batch)")
+    ap.add_argument("--decode", action="store_true",
+                    help="time one decoding step per layer instead (W=1 accumulate, evict one token, compact); "
+                         "a side measurement, not the headline metric")
+    ap.add_argument("--cache", type=int, default=1025, help="--decode: tokens in the cache when the step starts")
+    ap.add_argument("--batch", type=int, default=1, help="--decode: sequences")
     return ap.parse_args()
+
+
+def decode_step_bench(args, torch, obc):
+    """One decoding step of a Llama-3.1-8B-shaped layer in the paper's decoding setup (Appendix C: 4 sinks, 256
+    recent tokens, the rest heavy hitters): accumulate the new row's scores, evict one token per head, move the
+    cache and the scores.  Prints one JSON line of per-layer latencies in microseconds."""
+    dev = torch.device("cuda:0")
+    B, N, Hq, Hkv, d = args.batch, args.cache, 32, 8, 128
+    g = torch.Generator().manual_seed(7)
+    q = torch.randn(B, Hq, 1, d, generator=g).to(torch.bfloat16).to(dev)
+    k = torch.randn(B, Hkv, N, d, generator=g).to(torch.bfloat16).to(dev)
+    v = torch.randn(B, Hkv, N, d, generator=g).to(torch.bfloat16).to(dev)
+    var = obc.VARIANT_CODES[args.variant]
+    ws = torch.empty(obc.obc_score_workspace_bytes(B, N, 1, Hq, Hkv, d, obc.OBC_BF16, var), dtype=torch.uint8, device=dev)
+    run = torch.zeros(B, Hkv, N, dtype=torch.float32, device=dev)
+    keep = torch.empty(B, Hkv, N - 1, dtype=torch.int32, device=dev)
+    k_out = torch.empty(B, Hkv, N - 1, d, dtype=torch.bfloat16, device=dev)
+    v_out = torch.empty_like(k_out)
+    s_out = torch.empty(B, Hkv, N, dtype=torch.float32, device=dev)
+    sinks, recent = 4, 256
+    hh = N - 1 - sinks - recent
+
+    def score(i):
+        obc.obc_score(q, k, v, var, scores=run, workspace=ws, accumulate=True)
+
+    def step_gather(i):
+        score(i)
+        obc.obc_select_protected(run, hh, sinks, recent, 0, keep_idx=keep)
+        obc.obc_compact(k, v, keep, k_out=k_out, v_out=v_out)
+        obc.obc_compact_scores(run, keep, n_out=N, scores_out=s_out)
+
+    def step_inplace(i):
+        score(i)
+        obc.obc_select_protected(run, hh, sinks, recent, 0, keep_idx=keep)
+        obc.obc_compact_inplace(k, v, keep, scores=run)
+
+    for i in range(args.warmup):
+        step_gather(i)
+        step_inplace(i)
+    torch.cuda.synchronize()
+    it = max(args.steps, 50)
+    out = {"metric": "decode step latency per layer (W=1 accumulate + evict one + compact)", "unit": "us", "n_gpus": 1,
+           "steps": it, "warmup": args.warmup, "higher_is_better": False, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": "decode_llama8b_layer", "B": B, "Hq": Hq, "Hkv": Hkv, "d": d, "cache": N,
+                      "sinks": sinks, "recent": recent, "variant": args.variant},
+           "score_accumulate_us": round(timed(score, it, torch) * 1e3, 2),
+           "step_gather_us": round(timed(step_gather, it, torch) * 1e3, 2),
+           "step_inplace_us": round(timed(step_inplace, it, torch) * 1e3, 2)}
+    out["value"] = out["step_inplace_us"]
+    print(json.dumps(out))
 
 
 def timed(fn, iters, torch):
@@ -63,6 +118,9 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(3)
     obc.load_library()
+    if args.decode:
+        decode_step_bench(args, torch, obc)
+        return
     dev = torch.device("cuda:0")
     wl = synth.config(args.workload)
     B, Hq, Hkv, d, N, W = wl.B, wl.Hq, wl.Hkv, wl.d, wl.N, wl.W

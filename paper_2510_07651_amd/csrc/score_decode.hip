@@ -482,8 +482,11 @@ __global__ __launch_bounds__(kThreads) void decode_score(
 
     if (merge_here) {
         const float *part_head = part + (size_t)bh * splits * kG * part_stride(kD);
-        for (int e = threadIdx.x; e < G * kD; e += kThreads)
-            merge_few<kD, kNeedO>(part_head, splits, kG, e / kD, e % kD, vg, fin);
+#pragma unroll
+        for (int e0 = 0; e0 < kG * kD; e0 += kThreads) {       // unrolled: the loads of all passes go out together
+            const int e = e0 + threadIdx.x;
+            if (e < G * kD) merge_few<kD, kNeedO>(part_head, splits, kG, e / kD, e % kD, vg, fin);
+        }
     } else {
         const float *src = fin_global + (size_t)bh * kG * kFs;
         for (int e = threadIdx.x; e < G * kFs; e += kThreads) fin[e] = src[e];
