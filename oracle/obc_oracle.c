@@ -36,8 +36,14 @@
  * differences, brute force); q = 0 closed form; library attention
  * (torch scaled_dot_product_attention, fp64); token permutation equivariance;
  * GQA = sum of MHA heads; Eq. 6 literal form == completed-square form;
- * select vs a library stable sort; compaction vs fancy indexing.
+ * select vs a library stable sort; compaction vs fancy indexing; Eq. 4-6 in
+ * 50-digit arithmetic for a key that holds up to 1 - 1e-16 of a row's weight.
  * No function here is "parity unpinned".
+ *
+ * Arithmetic: fp64 throughout, every formula as printed, with one exception
+ * forced by fp64 itself: v_p - o_i for the row's largest-weight key is summed
+ * as sum_q A_iq (v_p - v_q) (equal because a softmax row sums to one), since
+ * the plain difference cancels as that weight tends to 1 (see obc_oracle_score).
  */
 #include <math.h>
 #include <stdint.h>
@@ -173,31 +179,48 @@ int obc_oracle_score(const double *q, const double *k, const double *v,
         double *z = (double *)malloc(sizeof(double) * (size_t)N);
         double *a = (double *)malloc(sizeof(double) * (size_t)N);
         double *o = (double *)malloc(sizeof(double) * (size_t)d);
+        double *dtop = (double *)malloc(sizeof(double) * (size_t)d);
         double *acc_v = hv + (size_t)bh * N, *acc_k = hk + (size_t)bh * N;
         double *acc_j = hj + (size_t)bh * N, *acc_x = hx + (size_t)bh * N;
         for (int r = 0; r < W; ++r) {               /* i = w..s, Eq. 9 */
             const int n_vis = len - W + r + 1;
             const double *q_row = q + ((size_t)bh * W + r) * d;
             attention_row(q_row, Kg, Vg, n_vis, d, z, a, o);
+            /*
+             * The key with the largest weight of the row.  As that weight tends to 1, o_i tends to
+             * v_p and the plain difference v_p - o_i loses eps / (1 - A_ip) of its relative
+             * accuracy, all of it once 1 - A_ip reaches 1e-16.  The weights of a row sum to one
+             * (Section 3), so v_p - o_i = sum_q A_iq (v_p - v_q) exactly: a sum of small terms
+             * whose q = p term is zero.  For this one key of the row the difference is formed
+             * that way, (1+Z) v - Z o as v + Z (v - o), and ||v||^2 - v.o as v.(v - o).
+             */
+            int p_top = 0;
+            for (int p = 1; p < n_vis; ++p) if (a[p] > a[p_top]) p_top = p;
+            for (int j = 0; j < d; ++j) dtop[j] = 0.0;
+            for (int qq = 0; qq < n_vis; ++qq) {
+                if (qq == p_top) continue;
+                for (int j = 0; j < d; ++j) dtop[j] += a[qq] * (Vg[(size_t)p_top * d + j] - Vg[(size_t)qq * d + j]);
+            }
             for (int p = 0; p < n_vis; ++p) {
                 const double *vp = Vg + (size_t)p * d;
                 const double A2 = a[p] * a[p];
-                double vv = 0.0, vmo2 = 0.0, vo = 0.0, sq = 0.0;
+                const int top = p == p_top;
+                double vv = 0.0, vmo2 = 0.0, vvmvo = 0.0, sq = 0.0;
                 for (int j = 0; j < d; ++j) {
-                    const double diff = vp[j] - o[j];
-                    const double comb = (1.0 + z[p]) * vp[j] - z[p] * o[j];
+                    const double diff = top ? dtop[j] : vp[j] - o[j];
+                    const double comb = top ? vp[j] + z[p] * dtop[j] : (1.0 + z[p]) * vp[j] - z[p] * o[j];
                     vv += vp[j] * vp[j];
                     vmo2 += diff * diff;
-                    vo += vp[j] * o[j];
+                    vvmvo += top ? vp[j] * dtop[j] : vp[j] * vp[j] - vp[j] * o[j];
                     sq += comb * comb;
                 }
                 acc_v[p] += A2 * vv;                       /* Eq. 4 */
                 acc_k[p] += A2 * z[p] * z[p] * vmo2;       /* Eq. 5 */
                 acc_j[p] += A2 * sq;                       /* Eq. 6, completed square */
-                acc_x[p] += 2.0 * A2 * z[p] * (vv - vo);   /* Eq. 6, cross term */
+                acc_x[p] += 2.0 * A2 * z[p] * vvmvo;       /* Eq. 6, cross term */
             }
         }
-        free(z); free(a); free(o);
+        free(z); free(a); free(o); free(dtop);
     }
 
     /* Score of KV head g = sum over its query heads h in H(g) (Appendix A.5, second display). */

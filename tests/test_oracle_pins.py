@@ -567,3 +567,46 @@ def test_compact_pads_negative_indices_with_zero_rows():
     np.testing.assert_array_equal(ko[0, 0, :3], k[0, 0, [0, 3, 8]])
     np.testing.assert_array_equal(vo[0, 1, :1], v[0, 1, [2]])
     assert np.all(ko[0, 0, 3:] == 0) and np.all(ko[0, 1, 1:] == 0) and np.all(vo[0, 1, 1:] == 0)
+
+
+@pytest.mark.parametrize("gain", [2.0, 4.0, 6.0, 8.0])
+def test_scores_of_a_key_that_takes_nearly_all_attention_match_50_digit_arithmetic(gain):
+    """Eq. 4-6 evaluated term by term in 50-digit arithmetic (mpmath) from the same inputs.  One key is aligned with
+    every window query, so that it holds 1 - 1e-4 .. 1 - 1e-16 of each row's weight and v_p - o_i is the difference of
+    two nearly equal vectors: plain fp64 loses eps / (1 - A) of that difference, the oracle must not."""
+    mp = pytest.importorskip("mpmath")
+    mp.mp.dps = 50
+    g = torch.Generator().manual_seed(91)
+    B, Hq, Hkv, N, W, d = 1, 2, 1, 24, 2, 8
+    q = torch.randn(B, Hq, W, d, generator=g, dtype=torch.float64)
+    k = torch.randn(B, Hkv, N, d, generator=g, dtype=torch.float64)
+    v = torch.randn(B, Hkv, N, d, generator=g, dtype=torch.float64)
+    u = torch.randn(d, generator=g, dtype=torch.float64)
+    q = q + 3.0 * u / u.norm() * d ** 0.5              # a direction all queries share
+    k[0, 0, 5] = gain * u / u.norm() * d ** 0.5         # key 5 points along it
+    qn, kn, vn = q.numpy(), k.numpy(), v.numpy()
+    sv, sk, sj = oracle.score(qn, kn, vn)
+    _, _, sj_literal = oracle.score(qn, kn, vn, joint_form=1)
+    M = lambda a: [mp.mpf(float(x)) for x in a]
+    ref = {"value": [mp.mpf(0)] * N, "key": [mp.mpf(0)] * N, "joint": [mp.mpf(0)] * N}
+    least_rest = mp.mpf(1)
+    for h in range(Hq):
+        for r in range(W):
+            n_vis = N - W + r + 1
+            z = [sum(a * b for a, b in zip(M(qn[0, h, r]), M(kn[0, 0, p]))) / mp.sqrt(d) for p in range(n_vis)]
+            zmax = max(z)
+            e = [mp.exp(x - zmax) for x in z]
+            tot = sum(e)
+            A = [x / tot for x in e]
+            least_rest = min(least_rest, 1 - max(A))
+            o = [sum(A[p] * mp.mpf(float(vn[0, 0, p, j])) for p in range(n_vis)) for j in range(d)]
+            for p in range(n_vis):
+                vp = M(vn[0, 0, p])
+                ref["value"][p] += A[p] ** 2 * sum(x * x for x in vp)
+                ref["key"][p] += A[p] ** 2 * z[p] ** 2 * sum((x - y) ** 2 for x, y in zip(vp, o))
+                ref["joint"][p] += A[p] ** 2 * sum(((1 + z[p]) * x - z[p] * y) ** 2 for x, y in zip(vp, o))
+    assert least_rest < mp.mpf(10) ** (-2 * gain + 1), "the case must be as lopsided as it claims (1 - A = %s)" % least_rest
+    for name, got in (("value", sv), ("key", sk), ("joint", sj), ("joint", sj_literal)):
+        for p in range(N):
+            want = ref[name][p]
+            assert abs(mp.mpf(float(got[0, 0, p])) - want) <= mp.mpf("1e-9") * want, (name, p, float(got[0, 0, p]), float(want))
