@@ -26,6 +26,9 @@ CASES = {w.name: w for w in [
     synth.Workload("d_mha_d64", B=2, Hq=3, Hkv=3, d=64, N=300, budget=30, seed=53, sinks=1, **W1),
     synth.Workload("d_g2_ragged", B=5, Hq=4, Hkv=2, d=128, N=2000, budget=1, seed=54, sinks=1, ragged=(1, 2000),
                    pad_nan=True, **W1),
+    synth.Workload("d_g3", B=2, Hq=6, Hkv=2, d=128, N=400, budget=40, seed=62, sinks=1, ragged=(100, 400), **W1),
+    synth.Workload("d_g5_d64", B=1, Hq=10, Hkv=2, d=64, N=700, budget=70, seed=63, sinks=2, outlier_channels=2, **W1),
+    synth.Workload("d_g6", B=1, Hq=12, Hkv=2, d=128, N=130, budget=13, seed=64, sinks=1, **W1),
     synth.Workload("d_g8_d64", B=1, Hq=8, Hkv=1, d=64, N=500, budget=50, seed=55, sinks=2, **W1),
     synth.Workload("d_long_separate_merge", B=2, Hq=8, Hkv=2, d=128, N=9000, budget=500, seed=56, sinks=4,
                    outlier_channels=4, ragged=(3000, 9000), pad_nan=True, **W1),

@@ -17,11 +17,11 @@ from parity_util import TOL, score_error, to_device
 pytestmark = pytest.mark.gpu
 
 
-def _draw(seed):
-    rng = np.random.default_rng(1000 + seed)
-    G = int(rng.choice([1, 2, 3, 4, 7, 8]))
+def _draw(seed, decode=False):
+    rng = np.random.default_rng((5000 if decode else 1000) + seed)
+    G = int(rng.choice([1, 2, 3, 4, 5, 6, 7, 8] if decode else [1, 2, 3, 4, 7, 8]))
     Hkv = int(rng.integers(1, 4))
-    W = int(rng.integers(1, min(64, 512 // G) + 1))
+    W = 1 if decode else int(rng.integers(1, min(64, 512 // G) + 1))
     dtype, d = [("bf16", 128), ("bf16", 128), ("bf16", 128), ("bf16", 64), ("fp32", 64), ("fp32", 128)][int(rng.integers(0, 6))]
     N = int(rng.integers(W, 2600))
     B = int(rng.integers(1, 4))
@@ -39,7 +39,16 @@ def _draw(seed):
 
 @pytest.mark.parametrize("seed", range(40))
 def test_random_shape(seed):
-    wl = _draw(seed)
+    _check(_draw(seed))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_decode_shape(seed):
+    """One-row windows (the decoding setting): the bf16 draws run on the decode kernels, the fp32 ones on the plain path."""
+    _check(_draw(seed, decode=True))
+
+
+def _check(wl):
     x = synth.make_inputs(wl)
     dev = to_device(x)
     lens = x["seq_lens"]
