@@ -48,6 +48,29 @@ def test_random_decode_shape(seed):
     _check(_draw(seed, decode=True))
 
 
+def _draw_long(seed):
+    """Caches of several sequence splits and many tiles on the matrix-core path (bf16, d = 128)."""
+    rng = np.random.default_rng(9000 + seed)
+    G = int(rng.choice([1, 2, 4, 7]))
+    Hkv = int(rng.integers(1, 3))
+    W = int(rng.integers(1, 49))
+    N = int(rng.integers(2600, 24000))
+    B = int(rng.integers(1, 3))
+    ragged = (int(rng.integers(max(W, N // 4), N + 1)), N) if rng.random() < 0.6 else None
+    min_len = ragged[0] if ragged else N
+    sinks = int(rng.integers(0, 5))
+    return synth.Workload("long%d" % seed, B=B, Hq=G * Hkv, Hkv=Hkv, d=128, N=N, W=W, dtype="bf16",
+                          budget=int(rng.integers(1, min_len + 1)), seed=9500 + seed, sinks=sinks,
+                          outlier_channels=int(rng.integers(0, 5)), needles=int(rng.integers(0, 9)), ragged=ragged,
+                          pad_nan=bool(ragged) and rng.random() < 0.5,
+                          shared_query=float(rng.choice([0.0, 0.0, 0.5, 1.0])))
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_long_shape(seed):
+    _check(_draw_long(seed))
+
+
 def _check(wl):
     x = synth.make_inputs(wl)
     dev = to_device(x)
