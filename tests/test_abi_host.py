@@ -38,6 +38,15 @@ def test_workspace_query_validation():
     assert obc.obc_score_workspace_bytes(1, 512, 16, 1, 1, 64, obc.OBC_F32, obc.OBC_ALL) % 256 == 0
     big = obc.obc_score_workspace_bytes(4, 32768, 32, 32, 8, 128, obc.OBC_BF16, obc.OBC_JOINT)
     assert 0 < big < (1 << 30)
+    # one-row windows: short caches plan the decode kernels' buffers (logits of G rows per head-token, range records),
+    # long ones the matrix-core path's; head_dim 64 and 8 query heads per KV head are served, fp32 goes the plain way
+    for args in ((1, 1025, 1, 32, 8, 128, obc.OBC_BF16, obc.OBC_JOINT), (4, 1025, 1, 28, 4, 128, obc.OBC_BF16, obc.OBC_ALL),
+                 (1, 131072, 1, 32, 8, 128, obc.OBC_BF16, obc.OBC_JOINT), (2, 3000, 1, 8, 1, 64, obc.OBC_BF16, obc.OBC_VALUE),
+                 (1, 1 << 21, 1, 8, 8, 64, obc.OBC_BF16, obc.OBC_KEY), (1, 1025, 1, 32, 8, 128, obc.OBC_F32, obc.OBC_JOINT)):
+        need = obc.obc_score_workspace_bytes(*args)
+        assert need > 0 and need % 256 == 0, args
+    short = obc.obc_score_workspace_bytes(1, 1025, 1, 32, 8, 128, obc.OBC_BF16, obc.OBC_JOINT)
+    assert short >= 8 * 1025 * 4 * 4                     # the stored logits alone
     bad = [
         (1, 512, 16, 3, 2, 64, obc.OBC_F32, obc.OBC_ALL, obc.OBC_EINVAL),        # Hq % Hkv != 0
         (1, 8, 16, 1, 1, 64, obc.OBC_F32, obc.OBC_ALL, obc.OBC_EINVAL),          # W > N
