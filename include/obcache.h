@@ -33,6 +33,12 @@
  *     detected on the host before anything is launched.
  *   - Same inputs give bit-identical outputs (no floating-point atomics).
  *   - The library targets gfx950 only and has no CPU fallback.
+ *   - obc_score picks its kernels from the shapes: bf16 with head_dim 128 runs on the matrix
+ *     cores; a one-row window (W = 1, the decoding case) over a bf16 cache of up to ~1e5
+ *     head-tokens runs on kernels shaped for memory round trips; everything else (fp32,
+ *     bf16 with head_dim 64 and W > 1) on general vector-ALU kernels.  The environment
+ *     variable OBC_SCORE_PATH = plain | mfma | decode pins a path where it applies (for
+ *     comparisons and tests); results agree within the tolerance of the dtype on all of them.
  */
 #ifndef OBCACHE_H_
 #define OBCACHE_H_
@@ -63,7 +69,7 @@ typedef enum {
 
 typedef enum {
     OBC_F32 = 0,   /* q,k,v fp32; head_dim 64 or 128; fp32 arithmetic */
-    OBC_BF16 = 1   /* q,k,v bf16; head_dim 128 on the matrix-core path (64 on the plain path); fp32 accumulation */
+    OBC_BF16 = 1   /* q,k,v bf16; head_dim 64 or 128; fp32 accumulation */
 } obc_dtype_t;
 
 #define OBC_MAX_RAGGED_BATCH 128  /* largest B accepted together with seq_lens_host */
