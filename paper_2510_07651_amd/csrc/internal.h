@@ -39,7 +39,6 @@ struct ScoreWorkspace {
     size_t row_const;  // float [B*Hkv*m_pad*4]  per padded row: 2*(max + log2 sum) in log2 units, ||o||^2, last visible key, spare
     size_t part_ml;    // float [B*Hkv*splits*m_pad*4]  per sequence split: row max (raw q.k), row sum, spare x2
     size_t special;    // float [B*Hkv*m_pad*4]  per padded row: separately scored top key (token or -1) and its value/key/joint terms
-    size_t dom_rows;   // int32 [B*Hkv*m_pad + B*Hkv]  per KV head: rows whose top key dominates (in row order), then the counts
     size_t part_o;     // float [B*Hkv*splits*m_pad*d]  per sequence split: unnormalised output
     size_t planes;     // float [n_chunks*nv*B*Hkv*N]   per row-chunk partial scores (only when n_chunks > 1)
     size_t total;

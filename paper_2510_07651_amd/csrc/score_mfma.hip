@@ -7,8 +7,8 @@
 //   sweep 1  (mfma_sweep1)   per (KV head, 128-row chunk, sequence split): S^T = K Q^T on
 //            the matrix cores, online softmax per row, O^T += V^T P^T on the matrix cores;
 //            emits a partial (row max, row sum, unnormalised O) per split.
-//   combine  (mfma_combine)  merges the splits: final max, sum, o_i (fp32 and bf16),
-//            ||o_i||^2, and the constants the second sweep needs per row.
+//   combine  (mfma_combine, mfma_combine_hold)  merges the splits: final sum, o_i as a pair
+//            of bf16 pieces, ||o_i||^2, and the constants the second sweep needs per row.
 //   sweep 2  (mfma_sweep2)   per (KV head, chunk, token range): Z = Q K^T and the cross
 //            terms O V^T on the matrix cores, with tokens on the lane axis of the
 //            accumulators so that the sum over window rows and query heads (Eq. 9,
@@ -35,6 +35,14 @@
 // ||v_p - o_i||^2 is evaluated as ||v_p||^2 - 2 v_p.o^_i + ||o^_i||^2 with o^_i the
 // two-piece value used by the matrix cores in BOTH the cross term and the norm, so the
 // expression is the exact squared distance to o^_i.
+//
+// Rows dominated by one key (an attention sink, the token's own key) would still lose
+// v_p - o_i of that key to cancellation: o_i is then v_p plus a small remainder.  The first
+// sweep therefore keeps, per row, the one key that may end up dominant out of its sums (a new
+// running maximum that clears the old one by ln 9: no other key can reach a share of 0.9), and the
+// combine step forms v_p - o_i = (1 - A_ip)(v_p - mean of the others) for that key directly.
+// The (row, key) pair is scored there in fp32 when its share is large, and the second sweep
+// skips it.  One pass serves every input: nothing is rescanned for rows that turn out dominated.
 //
 // A and Z never touch HBM.  All sums have a fixed order: results are bit-reproducible.
 #include <cstdlib>
@@ -64,10 +72,7 @@ constexpr float kInvSqrtD = 0.08838834764831845f;   // 1/sqrt(128)
 // rescale becomes rare instead of happening whenever any of a wave's 32 rows sees a new max.
 constexpr float kLazyRescale = 8.0f / (kLog2e * kInvSqrtD);   // in raw q.k units
 
-// Rows with A_top = 1 / row sum above this share of the attention are rescued (see below).
-constexpr float kDominantShare = 0.9f;
-
-// LDS map (bytes) of sweep 2 and the rescue sweep: two K tiles, then two V tiles.  Sweep 1 uses
+// LDS map (bytes) of sweep 2: two K tiles, then two V tiles.  Sweep 1 uses
 // the same 64 KB as a ring of four 8 KB K blocks followed by a ring of four V blocks.
 constexpr int kLdsK0 = 0, kLdsK1 = kTileBytes, kLdsV0 = 2 * kTileBytes, kLdsV1 = 3 * kTileBytes;
 constexpr int kLdsTiles = 4 * kTileBytes;           // 64 KB
@@ -99,7 +104,6 @@ __device__ __forceinline__ void dma16_based(const void *sbase, uint32_t voff, ui
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_off), "v"(voff), "s"(sbase) : "memory");
 }
 __device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-
 // Asynchronous copy of one 64-row tile.  Each wave issues four transfers; lane l of
 // transfer n lands at row 4 (4 wave + n) + l / 16, slot l % 16, and picks the global piece
 // that belongs in that slot.  Rows past `last_row` re-read `last_row` (memory beyond the
@@ -203,7 +207,30 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     return *(const uint32_t *)&r;
 }
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
-__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32); }
+// Lanes l and l + 32 of a wave hold the two halves of one row (sweep 1) or token (sweep 2).  One
+// register-to-register swap of the wave's halves gives every lane both values: no trip through the LDS crossbar.
+__device__ __forceinline__ void both_halves(float x, float &lower, float &upper) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    lower = __uint_as_float(r[0]);      // the value of lane l % 32
+    upper = __uint_as_float(r[1]);      // the value of lane l % 32 + 32
+}
+__device__ __forceinline__ float halves_sum(float x) { float a, b; both_halves(x, a, b); return a + b; }
+__device__ __forceinline__ float halves_max(float x) { float a, b; both_halves(x, a, b); return fmaxf(a, b); }
+// Sum over the 64 lanes of a wave, the same bits in every lane.  Lane pairings inside a row of 16 through the
+// data-parallel-primitive lane controls (neighbours, neighbouring pairs, mirror image inside 8 and inside 16:
+// register to register), then the row next door and the other half of the wave.  Call with every lane active.
+template <int kCtrl>
+__device__ __forceinline__ float dpp_pair_sum(float x) {
+    return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), kCtrl, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float wave_sum(float x) {
+    x = dpp_pair_sum<0xB1>(x);
+    x = dpp_pair_sum<0x4E>(x);
+    x = dpp_pair_sum<0x141>(x);
+    x = dpp_pair_sum<0x140>(x);
+    x += __shfl_xor(x, 16);
+    return halves_sum(x);
+}
 __device__ __forceinline__ f32x16 zero16() {
     f32x16 z;
 #pragma unroll
@@ -251,18 +278,71 @@ struct Sweep1Regs {
     float lsum;           // this lane's share of the running sum
     float alpha;          // rescale of oacc still owed from the previous step (1 = none)
     bool rescale;         // uniform: some row of the wave owes a rescale
+    // With kNeedO only: the row's candidate for a dominant key, kept out of lsum and oacc.
+    float cand_val;       // its raw q.k (-inf: none yet)
+    int cand_tok;         // its token (-1: none yet)
+    int n_ev;             // former candidates parked in this lane's LDS list, to be added back at the end
 };
+
+// A key can end up with more than a share s of a row's attention only if its logit exceeds every
+// other one by ln(s / (1 - s)); a new running maximum that clears the old one by less can never
+// get there and stays an ordinary key.  The margin below is the one for s = 0.9: rows without a held
+// key have no key above that share, which bounds the cancellation in v_p - o_i to a factor 10.
+constexpr float kCandMargin = 2.1972245773362196f / kInvSqrtD;   // ln(0.9 / 0.1), in raw q.k units
+constexpr float kSeparateShare = 0.5f;   // a candidate holding at least this share of its row is scored by the combine step
+constexpr int kEvents = 4;               // former candidates a lane can park
+
+// Adds a former candidate (token `tok`, raw logit `val`) back into this lane's sums: weight
+// exp2((val - ref_l) c2) into lsum (one half-wave only, the halves are added at the end) and
+// exp2((val - ref_o) c2) v_tok into the lane's 64 entries of O^T.
+__device__ __forceinline__ void add_back_fetch(uint2 (&x)[16], const char *vh, int tok, int half) {
+    const char *vrow = vh + (size_t)tok * kRowBytes;
+#pragma unroll
+    for (int ddb = 0; ddb < 4; ++ddb)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) x[ddb * 4 + r4] = *(const uint2 *)(vrow + (ddb * 32 + 8 * r4 + 4 * half) * 2);
+}
+
+__device__ __forceinline__ void add_back_apply(Sweep1Regs &R, const uint2 (&x)[16], float val, float ref_l, float ref_o,
+                                               int half) {
+    const float c2 = kLog2e * kInvSqrtD;
+    const float w_o = __builtin_amdgcn_exp2f((val - ref_o) * c2);
+    if (half == 0) R.lsum += __builtin_amdgcn_exp2f((val - ref_l) * c2);
+#pragma unroll
+    for (int ddb = 0; ddb < 4; ++ddb)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const uint2 w = x[ddb * 4 + r4];
+            R.oacc[ddb][4 * r4 + 0] = fmaf(w_o, __uint_as_float(w.x << 16), R.oacc[ddb][4 * r4 + 0]);
+            R.oacc[ddb][4 * r4 + 1] = fmaf(w_o, __uint_as_float(w.x & 0xffff0000u), R.oacc[ddb][4 * r4 + 1]);
+            R.oacc[ddb][4 * r4 + 2] = fmaf(w_o, __uint_as_float(w.y << 16), R.oacc[ddb][4 * r4 + 2]);
+            R.oacc[ddb][4 * r4 + 3] = fmaf(w_o, __uint_as_float(w.y & 0xffff0000u), R.oacc[ddb][4 * r4 + 3]);
+        }
+}
+
+__device__ __forceinline__ void add_back(Sweep1Regs &R, const char *vh, int tok, float val, float ref_l, float ref_o,
+                                         int half) {
+    uint2 x[16];
+    add_back_fetch(x, vh, tok, half);
+    add_back_apply(R, x, val, ref_l, ref_o, half);
+}
 
 // One pipeline step n of sweep 1 (PH = n mod 4 fixes every LDS slot at compile time):
 //   matrix cores: O^T += V^T P^T of block n-1, S^T = K Q^T of block n+1
 //   vector ALUs : online softmax of block n
 // Every step first waits for the two blocks it reads, meets the other waves at a barrier and
 // starts the loads of the blocks three steps ahead.
+//
+// With kNeedO (Eq. 5, 6) every row keeps its candidate for a dominant key (see kCandMargin) out of
+// its sums.  The step is then cut in two: K Q^T and the block's row maxima first; a vote whether
+// some row of the wave meets a new candidate in block n, and (rarely) the branch that deals with
+// it; then V^T P^T and the weights.  Without kNeedO the step is one basic block.
 template <int PH, bool kMasked, bool kNeedO>
 __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uint32_t lds0, int n, int t_begin,
                                             int t_end, int last_row, int vis, const char *kh, const char *vh,
                                             const int (&koff)[8], const int (&voff)[4], const uint32_t (&kdoff)[2],
-                                            const uint32_t (&vdoff)[2], int wave, int lane, bool wave_active) {
+                                            const uint32_t (&vdoff)[2], int wave, int lane, bool wave_active,
+                                            int2 *events) {
     // K and V blocks live in rings of four 8 KB slots each (block j in slot j mod 4): K block
     // n+1 and V block n-1, both started three steps ago, are waited for here while the two
     // younger batches stay in flight; then K block n+4 and V block n+2 start in the slots
@@ -281,7 +361,6 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
     if (!wave_active) return;
     // The running max moved in the previous step: bring the accumulated O^T (blocks <= n-2)
     // to the new reference before block n-1, whose weights already use it, is added.
-    // Kept as the only branch of the step so that everything below is one basic block.
     if (kNeedO && R.rescale) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
@@ -289,17 +368,6 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
             for (int r = 0; r < 16; ++r) R.oacc[i][r] *= R.alpha;
     }
 
-    // ---- matrix cores: block n-1 ----
-    if (kNeedO) {
-#pragma unroll
-        for (int ddb = 0; ddb < 4; ++ddb)
-#pragma unroll
-            for (int sx = 0; sx < 2; ++sx) {
-                const bf16x8 a = lds_read_vt(smem + kVBase + 16 * sx * kRowBytes + voff[ddb]);
-                R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.phi[sx].v, R.oacc[ddb], 0, 0, 0);
-                R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.plo[sx].v, R.oacc[ddb], 0, 0, 0);
-            }
-    }
     // ---- matrix cores: block n+1 ----
     f32x16 s_next = zero16();
 #pragma unroll
@@ -321,7 +389,51 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
 #pragma unroll
     for (int r = 3; r < 15; r += 2) mx = max3(mx, s[r], s[r + 1]);
     mx = fmaxf(mx, s[15]);
-    mx = fmaxf(mx, other_half(mx));
+    mx = halves_max(mx);
+    if (kNeedO) {
+        // Rows whose block maximum clears their running maximum by the margin take the block's first key of
+        // that logit as their candidate: its logit becomes -inf before the weights are formed, so it never
+        // enters this block's P or sum, and the previous candidate is parked (or, with the list full, added
+        // back on the spot).  (-inf + margin = -inf: a row's first visible key always is a candidate.)
+        const float m_true_before = R.m_true;
+        if (__any(mx > m_true_before + kCandMargin)) {                 // uniform
+            if (mx > m_true_before + kCandMargin) {
+                uint32_t hit = 0;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) hit |= s[r] == mx ? (1u << r) : 0u;
+                // (a lane's registers ascend with their tokens: its lowest set bit is its first such key)
+                const int rc_own = hit ? __builtin_ctz(hit) : 0;
+                const int off_own = hit ? 8 * (rc_own >> 2) + 4 * half + (rc_own & 3) : 64;
+                float off_lower, off_upper;
+                both_halves(__int_as_float(off_own), off_lower, off_upper);      // (bits only)
+                const int off_first = min(__float_as_int(off_lower), __float_as_int(off_upper));
+                const int rc = off_own == off_first ? rc_own : -1;              // its register, if in this lane
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[r] = r == rc ? -INFINITY : s[r];
+                if (R.cand_tok >= 0) {                                 // the previous candidate is an ordinary key after all
+                    if (R.n_ev < kEvents) {
+                        events[R.n_ev] = make_int2(R.cand_tok, __float_as_int(R.cand_val));
+                        R.n_ev += 1;
+                    } else {
+                        // (sum and O^T both stand at the current reference: the owed rescale was applied above)
+                        add_back(R, vh, R.cand_tok, R.cand_val, R.m_ref, R.m_ref, half);
+                    }
+                }
+                R.cand_tok = t_begin + n * 32 + off_first;
+                R.cand_val = mx;
+            }
+        }
+        // ---- matrix cores: block n-1 ----
+#pragma unroll
+        for (int ddb = 0; ddb < 4; ++ddb)
+#pragma unroll
+            for (int sx = 0; sx < 2; ++sx) {
+                const bf16x8 a = lds_read_vt(smem + kVBase + 16 * sx * kRowBytes + voff[ddb]);
+                R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.phi[sx].v, R.oacc[ddb], 0, 0, 0);
+                R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.plo[sx].v, R.oacc[ddb], 0, 0, 0);
+            }
+    }
+    // The reference may follow a candidate's logit: it only has to bound the weights from above.
     R.m_true = fmaxf(R.m_true, mx);
     const bool moved = mx > R.m_ref + kLazyRescale;                    // also true for the first visible key
     const float m_new = moved ? mx : R.m_ref;
@@ -355,22 +467,26 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
         R.rescale = __any(moved);      // uniform and rare once the running max has settled
     }
     R.s_cur = s_next;
-    interleave_hint<kNeedO ? 24 : 8, kNeedO ? 6 : 12, kNeedO ? 2 : 1>();
+    // (the two-part step is left to the compiler's own schedule: it measured faster that way)
+    if (!kNeedO) interleave_hint<8, 12, 1>();
 }
 
 // Grid: x = sequence split, y = 128-row chunk, z = (b, KV head).
+// With kNeedO every row keeps its candidate for a dominant key (see kCandMargin) out of its sums and
+// reports it with the partial record; the combine step then forms v_cand - o_i without
+// cancellation for every row, and no row ever needs a second pass.
 template <bool kNeedO>
 __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__restrict__ q,
                                                            const uint16_t *__restrict__ k,
                                                            const uint16_t *__restrict__ v, int N, int W, int Hq,
                                                            int Hkv, int ragged, SeqLens lens, int split_len,
                                                            int n_splits, int m_pad, float *__restrict__ part_ml,
-                                                           float *__restrict__ part_o,
-                                                           int32_t *__restrict__ dom_count) {
+                                                           float *__restrict__ part_o) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
+    __shared__ int2 ev_list[kNeedO ? kThreads * kEvents : 1];   // per lane: parked former candidates (token, logit bits)
+    int2 *events = ev_list + (kNeedO ? threadIdx.x * kEvents : 0);
 
     const int split = blockIdx.x, chunk = blockIdx.y, bg = blockIdx.z;
-    if (split == 0 && chunk == 0 && threadIdx.x == 0) dom_count[bg] = 0;   // filled by the combine step
     const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv, M = G * W;
     const int len = seq_len_of(lens, ragged, b, N);
     const int t_begin = split * split_len;
@@ -421,6 +537,9 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
     R.lsum = 0.f;
     R.alpha = 1.0f;
     R.rescale = false;
+    R.cand_val = -INFINITY;
+    R.cand_tok = -1;
+    R.n_ev = 0;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) settle(R.q[kk]);
 
@@ -452,7 +571,7 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
     const int n_total = (n_blk + 3) & ~3;
     int n_plain = (vis_min + 1 - t_begin) / 32;       // leading blocks every row of this wave sees in full
     n_plain = max(0, min(n_plain, n_blk)) & ~3;
-#define OBC_S1_ARGS smem, lds0, n, t_begin, t_end, len - 1, vis, kh, vh, koff, voff, kdoff, vdoff, wave, lane, wave_active
+#define OBC_S1_ARGS smem, lds0, n, t_begin, t_end, len - 1, vis, kh, vh, koff, voff, kdoff, vdoff, wave, lane, wave_active, events
     int n = 0;
     for (; n < n_plain; n += 4) {
         sweep1_step<0, false, kNeedO>(R, OBC_S1_ARGS); ++n;
@@ -467,6 +586,26 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
         sweep1_step<3, true, kNeedO>(R, OBC_S1_ARGS); n -= 3;
     }
 #undef OBC_S1_ARGS
+    // A final candidate that holds less than half of its own split's weight cannot dominate the
+    // row; it joins the parked former candidates, which are ordinary keys and are added back below, now that
+    // the reference is final.  The first one's value row is fetched ahead of the waits that follow.
+    uint2 first_row[16];
+    int2 first_ev = make_int2(-1, 0);
+    if (kNeedO && wave_active) {
+        const float c2 = kLog2e * kInvSqrtD;
+        const float l_rest = halves_sum(R.lsum);
+        if (R.cand_tok >= 0 && __builtin_amdgcn_exp2f((R.cand_val - R.m_ref) * c2) < l_rest) {
+            if (R.n_ev < kEvents) {
+                events[R.n_ev] = make_int2(R.cand_tok, __float_as_int(R.cand_val));
+                R.n_ev += 1;
+                R.cand_tok = -1;
+            }
+        }
+        if (R.n_ev > 0) {
+            first_ev = events[0];
+            add_back_fetch(first_row, vh, first_ev.x, half);
+        }
+    }
     wait_async_loads();        // the blocks fetched past the end must have landed before the LDS is given back
     if (!wave_active) return;
     if (kNeedO) {      // drain: P V of the last block (n_total - 1, in slot 3 of the V ring)
@@ -486,12 +625,23 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
             }
     }
 
-    const float lrow = R.lsum + other_half(R.lsum);
+    if (kNeedO) {
+        if (first_ev.x >= 0) add_back_apply(R, first_row, __int_as_float(first_ev.y), R.m_ref, R.m_ref, half);
+        for (int e = 1; e < kEvents; ++e) {
+            if (!__any(e < R.n_ev)) break;       // uniform
+            if (e < R.n_ev) {
+                const int2 ev = events[e];
+                add_back(R, vh, ev.x, __int_as_float(ev.y), R.m_ref, R.m_ref, half);
+            }
+        }
+    }
+    const float lrow = halves_sum(R.lsum);
     const size_t prow = ((size_t)bg * n_splits + split) * m_pad + row;
     if (half == 0) {
         part_ml[prow * 4 + 0] = R.m_ref;         // raw q.k units; -inf when the split holds no visible key
         part_ml[prow * 4 + 1] = lrow;
-        part_ml[prow * 4 + 2] = R.m_true;
+        part_ml[prow * 4 + 2] = kNeedO ? R.cand_val : R.m_true;
+        part_ml[prow * 4 + 3] = __int_as_float(kNeedO ? R.cand_tok : 0);
     }
     if (kNeedO) {
         float *dst = part_o + prow * kD;
@@ -509,21 +659,77 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
 // ------------------------------------------------------------------------------------
 // Combine: one 128-thread block per (KV head, padded row); thread = head_dim element.
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ part_ml,
-                                                    const float *__restrict__ part_o, int N, int W, int Hq, int Hkv,
+// Variants that need no o_i (Eq. 4, Eq. 8 and its l1-weighted form): the splits' row sums are merged into the
+// one constant per row the second sweep turns logits into weights with.
+__global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ part_ml, int N, int W, int Hq, int Hkv,
                                                     int ragged, SeqLens lens, int split_len, int n_splits,
-                                                    int m_pad, int need_o, float *__restrict__ row_max,
-                                                    float *__restrict__ row_sum, float *__restrict__ out_f32,
-                                                    uint16_t *__restrict__ out_bf16, float *__restrict__ row_const,
-                                                    float *__restrict__ special, int32_t *__restrict__ dom_rows,
-                                                    int32_t *__restrict__ dom_count) {
-    __shared__ float red[2];
+                                                    int m_pad, uint16_t *__restrict__ out_bf16,
+                                                    float *__restrict__ row_const, float *__restrict__ special) {
     const int row = blockIdx.x, bg = blockIdx.y;
-    const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv, M = G * W;
+    const int b = bg / Hkv, G = Hq / Hkv, M = G * W;
     const int len = seq_len_of(lens, ragged, b, N);
     const int dd = threadIdx.x;
     const size_t crow = (size_t)bg * m_pad + row;
     const size_t lo_plane = (size_t)gridDim.y * m_pad * kD;   // residual pieces follow the high pieces
+    out_bf16[crow * kD + dd] = 0;                     // (no cross term: the operand is never read, and stays defined)
+    out_bf16[lo_plane + crow * kD + dd] = 0;
+    if (dd != 0) return;
+    special[crow * 4 + 0] = __int_as_float(-1);       // no separately scored (row, token) pair
+    row_const[crow * 4 + 1] = 0.f;
+    row_const[crow * 4 + 3] = 0.f;
+    if (row >= M) {                                   // padded row: weightless in the second sweep
+        row_const[crow * 4 + 0] = 1e30f;
+        row_const[crow * 4 + 2] = __int_as_float(-1);
+        return;
+    }
+    const int live_splits = (len + split_len - 1) / split_len;
+    const float c2 = kLog2e * kInvSqrtD;
+    // Splits are merged sixteen at a time, every load of a batch issued before the first use.  The running sum
+    // follows the running max of the raw dot products; a split's sum is relative to its own reference.
+    float m_raw = -INFINITY, l = 0.f;
+    for (int s0 = 0; s0 < live_splits; s0 += 16) {
+        float4 ml[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j)      // (clamped slots are ignored below)
+            ml[j] = ((const float4 *)part_ml)[((size_t)bg * n_splits + min(s0 + j, live_splits - 1)) * m_pad + row];
+        float m_new = m_raw;
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            if (s0 + j < live_splits) m_new = fmaxf(m_new, ml[j].z);
+        l *= m_raw == -INFINITY ? 0.f : exp2f((m_raw - m_new) * c2);
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            if (s0 + j >= live_splits) continue;
+            l = fmaf(ml[j].x == -INFINITY ? 0.f : exp2f((ml[j].x - m_new) * c2), ml[j].y, l);
+        }
+        m_raw = m_new;
+    }
+    row_const[crow * 4 + 0] = 2.0f * (m_raw * c2 + log2f(l));   // A_ip^2 = exp2(2 log2e Z_ip - this)
+    row_const[crow * 4 + 2] = __int_as_float(len - W + (row % W));
+}
+
+// Variants that need o_i (Eq. 5, 6): the same grid.  Every split reports, per row, its sums without its
+// candidate key and the candidate itself.  The candidate with the largest logit (the first split on
+// ties) stays held out; the others are ordinary keys and are added back from the value cache.  With
+// l' and O' the sums over every key but that one, relative to a common reference T,
+//     w = exp2((z_cand - T) c2),   A_cand = w / (w + l'),
+//     v_cand - o_i = l' / (w + l') * (v_cand - O' / l'),      o_i = v_cand - (v_cand - o_i)
+// without cancellation however much of the row's attention the candidate holds.  A candidate that
+// holds a large share is scored here from these (`special`) and skipped by the second sweep.
+__global__ __launch_bounds__(128) void mfma_combine_hold(const uint16_t *__restrict__ v,
+                                                         const float *__restrict__ part_ml,
+                                                         const float *__restrict__ part_o, int N, int W, int Hq,
+                                                         int Hkv, int ragged, SeqLens lens, int split_len,
+                                                         int n_splits, int m_pad, uint16_t *__restrict__ out_bf16,
+                                                         float *__restrict__ row_const,
+                                                         float *__restrict__ special) {
+    __shared__ float red[4][2];
+    const int row = blockIdx.x, bg = blockIdx.y;
+    const int b = bg / Hkv, G = Hq / Hkv, M = G * W;
+    const int len = seq_len_of(lens, ragged, b, N);
+    const int dd = threadIdx.x;
+    const size_t crow = (size_t)bg * m_pad + row;
+    const size_t lo_plane = (size_t)gridDim.y * m_pad * kD;
     if (row >= M) {                                   // padded row: weightless in the second sweep
         out_bf16[crow * kD + dd] = 0;
         out_bf16[lo_plane + crow * kD + dd] = 0;
@@ -538,351 +744,110 @@ __global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ pa
     }
     const int live_splits = (len + split_len - 1) / split_len;
     const float c2 = kLog2e * kInvSqrtD;
-    // Splits are merged sixteen at a time, every load of a batch issued before the first use,
-    // so that a row costs one memory round trip per batch.  The running sums follow the
-    // running max of the raw dot products; a split's sums are relative to its own reference.
-    float m_raw = -INFINITY, l = 0.f, o = 0.f;
-    for (int s0 = 0; s0 < live_splits; s0 += 16) {
-        float4 ml[16];
-        float po[16];
+    const uint16_t *vg = v + (size_t)bg * N * kD;
+    // First the common reference T (no sum lies more than the lazy-rescale slack above its own
+    // reference, so the largest reference or candidate logit will do) and the winning candidate.
+    // The first 16 splits' records and sums are fetched in one go and stay in registers.
+    float T = -INFINITY, c_val = -INFINITY;
+    int c_tok = -1, s_star = -1;
+    float4 ml[16];
+    float po[16];
 #pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int s = min(s0 + j, live_splits - 1);       // clamped slots are ignored below
-            const size_t prow = ((size_t)bg * n_splits + s) * m_pad + row;
-            ml[j] = ((const float4 *)part_ml)[prow];
-            po[j] = need_o ? part_o[prow * kD + dd] : 0.f;
-        }
-        float m_new = m_raw;
+    for (int j = 0; j < 16; ++j) {
+        const size_t prow = ((size_t)bg * n_splits + min(j, live_splits - 1)) * m_pad + row;
+        ml[j] = ((const float4 *)part_ml)[prow];
+        po[j] = part_o[prow * kD + dd];
+    }
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+        if (j >= live_splits) continue;
+        T = fmaxf(T, fmaxf(ml[j].x, ml[j].z));
+        const int tok = __float_as_int(ml[j].w);
+        if (tok >= 0 && ml[j].z > c_val) { c_val = ml[j].z; c_tok = tok; s_star = j; }
+    }
+    for (int s0 = 16; s0 < live_splits; s0 += 16) {
+        float4 mm[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j)
-            if (s0 + j < live_splits) m_new = fmaxf(m_new, ml[j].z);
-        const float keep = m_raw == -INFINITY ? 0.f : exp2f((m_raw - m_new) * c2);
-        l *= keep;
-        o *= keep;
+            mm[j] = ((const float4 *)part_ml)[((size_t)bg * n_splits + min(s0 + j, live_splits - 1)) * m_pad + row];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             if (s0 + j >= live_splits) continue;
-            const float w = ml[j].x == -INFINITY ? 0.f : exp2f((ml[j].x - m_new) * c2);
+            T = fmaxf(T, fmaxf(mm[j].x, mm[j].z));
+            const int tok = __float_as_int(mm[j].w);
+            if (tok >= 0 && mm[j].z > c_val) { c_val = mm[j].z; c_tok = tok; s_star = s0 + j; }
+        }
+    }
+    const float vt = c_tok >= 0 ? bf16_bits_to_float(vg[(size_t)c_tok * kD + dd]) : 0.f;
+    float l = 0.f, o = 0.f;
+    for (int s0 = 0; s0 < live_splits; s0 += 16) {
+        float vo[16];
+        if (s0 > 0) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {         // (the records are in cache from the pass above)
+                const size_t prow = ((size_t)bg * n_splits + min(s0 + j, live_splits - 1)) * m_pad + row;
+                ml[j] = ((const float4 *)part_ml)[prow];
+                po[j] = part_o[prow * kD + dd];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int tok = __float_as_int(ml[j].w);
+            const bool back = s0 + j < live_splits && s0 + j != s_star && tok >= 0;
+            vo[j] = back ? bf16_bits_to_float(vg[(size_t)tok * kD + dd]) : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            if (s0 + j >= live_splits) continue;
+            const float w = ml[j].x == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((ml[j].x - T) * c2);
             l = fmaf(w, ml[j].y, l);
             o = fmaf(w, po[j], o);
+            if (s0 + j != s_star && __float_as_int(ml[j].w) >= 0) {   // this split's candidate is an ordinary key
+                const float wc = __builtin_amdgcn_exp2f((ml[j].z - T) * c2);
+                l += wc;
+                o = fmaf(wc, vo[j], o);
+            }
         }
-        m_raw = m_new;
     }
-    const float m = m_raw * c2;                       // log2 units
-    o = o / l;
-    // o^ = hi + lo, the pair of bf16 pieces the second sweep feeds to the matrix cores.
-    const uint16_t ob = (uint16_t)(__float_as_uint(o) >> 16);
+    // (no split may have kept a candidate: then w = 0 and o_i = O' / l' as usual)
+    const float wc = c_tok >= 0 ? __builtin_amdgcn_exp2f((c_val - T) * c2) : 0.f;
+    const float ltot = wc + l;
+    const float inv = 1.0f / ltot;
+    const float rest = l > 0.f ? o / l : 0.f;
+    const float diff = (l * inv) * (vt - rest);      // (v_cand - o_i)[dd]
+    const float oi = vt - diff;
+    const float z = c_val * kInvSqrtD;               // Z of the (row, candidate) pair
+    const float comb = fmaf(z, diff, vt);            // ((1+Z) v_cand - Z o_i)[dd]
+    const uint16_t ob = (uint16_t)(__float_as_uint(oi) >> 16);
     const float ohi = bf16_bits_to_float(ob);
-    const uint16_t olo = (uint16_t)(pack_bf16(o - ohi, 0.f) & 0xffffu);
+    const uint16_t olo = (uint16_t)(pack_bf16(oi - ohi, 0.f) & 0xffffu);
     const float of = ohi + bf16_bits_to_float(olo);
-    float sq = of * of;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) sq += __shfl_xor(sq, off);
-    if ((dd & 63) == 0) red[dd >> 6] = sq;
+    // A candidate with a small share is scored by the second sweep like any other key (its o_i is exact either
+    // way); one that may dominate is scored here and skipped there.  (Uniform: every thread holds the same sums.)
+    const float a = wc * inv;
+    const bool separate = a >= kSeparateShare;
+    const float oo = wave_sum(of * of);
+    if ((dd & 63) == 0) red[0][dd >> 6] = oo;
+    if (separate) {
+        const float s1 = wave_sum(vt * vt), s2 = wave_sum(diff * diff), s3 = wave_sum(comb * comb);
+        if ((dd & 63) == 0) { red[1][dd >> 6] = s1; red[2][dd >> 6] = s2; red[3][dd >> 6] = s3; }
+    }
     __syncthreads();
-    const size_t grow = ((size_t)b * Hq + (size_t)g * G) * W + row;
-    out_f32[grow * kD + dd] = o;
     out_bf16[crow * kD + dd] = minus_twice_bf16(ob);
     out_bf16[lo_plane + crow * kD + dd] = minus_twice_bf16(olo);
     if (dd == 0) {
-        row_max[grow] = m * 0.6931471805599453f;      // natural-log units
-        row_sum[grow] = l;
-        row_const[crow * 4 + 0] = 2.0f * (m + log2f(l));   // A_ip^2 = exp2(2 log2e Z_ip - this)
-        row_const[crow * 4 + 1] = red[0] + red[1];         // ||o^_i||^2
+        const float a2 = a * a;
+        row_const[crow * 4 + 0] = 2.0f * (T * c2 + log2f(ltot));   // A_ip^2 = exp2(2 log2e Z_ip - this)
+        row_const[crow * 4 + 1] = red[0][0] + red[0][1];           // ||o^_i||^2
         row_const[crow * 4 + 2] = __int_as_float(len - W + (row % W));
-        row_const[crow * 4 + 3] = m_raw;
-        special[crow * 4 + 0] = __int_as_float(-1);        // no separately scored (row, token) pair yet
-        // Rows whose top key dominates join the KV head's rescue list (any order: each row is
-        // rescued on its own; the count was cleared by sweep 1).
-        if (need_o && l * kDominantShare < 1.0f) dom_rows[crow - row + atomicAdd(&dom_count[bg], 1)] = row;
-    }
-}
-
-// ------------------------------------------------------------------------------------
-// Rescue of dominant rows
-// ------------------------------------------------------------------------------------
-// A row whose top key holds almost all of its attention (A_top = 1 / row sum > 0.9; the
-// top is then unique) has o_i ~ v_top, and fp32 sums that contain the top key's weight 1
-// cannot resolve v_top - o_i: the expanded norm loses its last digits near A_top ~ 0.99,
-// so rows are taken out well before that.  Such rows are rare (retrieval-like heads).  They are
-// listed per KV head by the combine step and swept once more with the row max known: the top key is left
-// out of the sums, which gives l' = sum_{q != top} exp(z_q - z_top) and O' = sum_{q != top}
-// exp(z_q - z_top) v_q, and then exactly
-//     v_top - o_i = l' / (1 + l') * (v_top - O' / l'),      o_i = v_top - (v_top - o_i).
-// The (row, top key) pair is scored from these in fp32 (`special`), the second sweep skips
-// that pair and adds the stored values, and uses the refreshed o_i for all other keys.
-
-// How a KV head's rescue work is cut up, as a function of the length of its dominant list.
-struct RescueLayout {
-    int list_chunks;   // 128-row chunks the list needs
-    int fine;          // sub-ranges every sequence split is cut into (spare chunk indices of the grid)
-    int sub_len;       // tokens per sub-range, a multiple of the tile
-    int list_rows;     // list positions stored per sub-range: min(list_chunks * 128, m_pad)
-};
-__device__ __forceinline__ RescueLayout rescue_layout(int count, int m_pad, int split_len) {
-    RescueLayout lay;
-    lay.list_chunks = (count + 127) / 128;
-    lay.fine = max(1, (m_pad / 128) / lay.list_chunks);
-    lay.sub_len = ((split_len + lay.fine - 1) / lay.fine + kTileTok - 1) / kTileTok * kTileTok;
-    lay.list_rows = min(lay.list_chunks * 128, m_pad);
-    return lay;
-}
-// Row of the partial-result arrays for (sub-split, list position): the head's share of the
-// arrays, n_splits * m_pad rows, is re-cut as [n_splits * fine][list_rows]; it fits because
-// fine * list_rows <= m_pad (fine > 1 only when fine * list_chunks * 128 <= m_pad).
-__device__ __forceinline__ size_t rescue_partial_row(const RescueLayout &lay, int bg, int n_splits, int m_pad,
-                                                     int sub_split, int slot) {
-    return (size_t)bg * n_splits * m_pad + (size_t)sub_split * lay.list_rows + slot;
-}
-
-// Grid: x = sequence split, y = 128-row chunk of the dominant list (or token sub-range, see
-// RescueLayout), z = (b, KV head).
-__global__ __launch_bounds__(kThreads, 2) void mfma_rescue_sweep(const uint16_t *__restrict__ q,
-                                                                 const uint16_t *__restrict__ k,
-                                                                 const uint16_t *__restrict__ v, int N, int W, int Hq,
-                                                                 int Hkv, int ragged, SeqLens lens, int split_len,
-                                                                 int n_splits, int m_pad,
-                                                                 const int32_t *__restrict__ dom_rows,
-                                                                 const int32_t *__restrict__ dom_count,
-                                                                 const float *__restrict__ row_const,
-                                                                 float *__restrict__ part_ml,
-                                                                 float *__restrict__ part_o) {
-    extern __shared__ __attribute__((aligned(1024))) char smem[];
-    const int split = blockIdx.x, bg = blockIdx.z;
-    const int count = dom_count[bg];
-    if (count == 0) return;                                      // uniform
-    // The grid has one y index per 128-row chunk of the longest possible list.  A shorter
-    // list needs fewer chunks; the spare y indices then subdivide every split's token range,
-    // so that a handful of dominant rows still spreads over the whole launch.
-    const RescueLayout lay = rescue_layout(count, m_pad, split_len);
-    const int chunk = blockIdx.y % lay.list_chunks, sub = blockIdx.y / lay.list_chunks;
-    if (sub >= lay.fine) return;                                 // uniform
-    const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv;
-    const int len = seq_len_of(lens, ragged, b, N);
-    const int t_begin = split * split_len + sub * lay.sub_len;
-    const int t_stop = min((split + 1) * split_len, len);
-    if (t_begin >= t_stop) return;
-    const int t_end = min(t_begin + lay.sub_len, t_stop);
-
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63, half = lane >> 5;
-    const int slot = chunk * 128 + wave * 32 + (lane & 31);      // position in the dominant list
-    const bool wave_active = chunk * 128 + wave * 32 < count;    // uniform
-    const bool row_valid = slot < count;
-    const int row = row_valid ? dom_rows[(size_t)bg * m_pad + slot] : 0;
-    const int vis = row_valid ? len - W + (row % W) : -1;        // unused list slots see nothing
-    const float m_raw = row_const[((size_t)bg * m_pad + row) * 4 + 3];
-    const float c2 = kLog2e * kInvSqrtD, mref = m_raw * c2;
-
-    const char *kh = (const char *)k + (size_t)bg * N * kRowBytes;
-    const char *vh = (const char *)v + (size_t)bg * N * kRowBytes;
-    const uint32_t lds0 = lds_offset_of(smem);
-    int koff[8], voff[4];
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) koff[kk] = row_piece_offset(lane, kk);
-#pragma unroll
-    for (int ddb = 0; ddb < 4; ++ddb) voff[ddb] = vt_piece_offset(lane, ddb);
-
-    bf16x8 qreg[8];
-    {
-        const char *qrow = (const char *)q + (((size_t)b * Hq + (size_t)g * G) * W + row) * kRowBytes;
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            if (row_valid) qreg[kk] = *(const bf16x8 *)(qrow + (2 * kk + half) * 16);
-            else qreg[kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        row_const[crow * 4 + 3] = 0.f;
+        special[crow * 4 + 0] = __int_as_float(separate ? c_tok : -1);
+        if (separate) {
+            special[crow * 4 + 1] = a2 * (red[1][0] + red[1][1]);             // Eq. 4 term of the pair
+            special[crow * 4 + 2] = a2 * z * z * (red[2][0] + red[2][1]);     // Eq. 5 term
+            special[crow * 4 + 3] = a2 * (red[3][0] + red[3][1]);             // Eq. 6 term (completed square)
         }
     }
-    f32x16 oacc[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) oacc[i] = zero16();
-    float lsum = 0.f;
-    int n_top = 0, top_tok = -1;
-
-    const int n_tiles = (t_end - t_begin + kTileTok - 1) / kTileTok;
-    uint32_t kdoff[4], vdoff[4];
-    tile_lane_offsets<kXor16>(kdoff, wave, lane);
-    tile_lane_offsets<kRot4>(vdoff, wave, lane);
-    tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane, kdoff);
-    tile_load_async<kRot4>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane, vdoff);
-    for (int it = 0; it < n_tiles; ++it) {
-        wait_async_loads();
-        __syncthreads();            // tile `it` is in LDS; everyone is done with the other slots
-        if (it + 1 < n_tiles) {
-            tile_load_async<kXor16>(kh, t_begin + (it + 1) * kTileTok, len - 1, lds0 + (((it + 1) & 1) ? kLdsK1 : kLdsK0), wave, lane, kdoff);
-            tile_load_async<kRot4>(vh, t_begin + (it + 1) * kTileTok, len - 1, lds0 + (((it + 1) & 1) ? kLdsV1 : kLdsV0), wave, lane, vdoff);
-        }
-        if (!wave_active) continue;
-        const char *ktile = smem + ((it & 1) ? kLdsK1 : kLdsK0);
-        const char *vtile = smem + ((it & 1) ? kLdsV1 : kLdsV0);
-#pragma unroll
-        for (int tb = 0; tb < 2; ++tb) {
-            // Same operands, same order as sweep 1: the raw dot products repeat bit for bit,
-            // so the top key is the one whose value equals the stored row max.
-            f32x16 s = zero16();
-#pragma unroll
-            for (int kk = 0; kk < 8; ++kk) {
-                const bf16x8 a = lds_read16(ktile + tb * 32 * kRowBytes + koff[kk]);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[kk], s, 0, 0, 0);
-            }
-            const int tok0 = t_begin + it * kTileTok + tb * 32;
-            float p[16];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int tok = tok0 + 8 * (r >> 2) + 4 * half + (r & 3);
-                const bool seen = tok <= vis && tok < t_end;
-                const bool top = seen && s[r] == m_raw;
-                p[r] = (seen && !top) ? __builtin_amdgcn_exp2f(fmaf(s[r], c2, -mref)) : 0.f;
-                lsum += p[r];
-                if (top) { ++n_top; top_tok = tok; }
-            }
-            PiecePair phi[2], plo[2];
-#pragma unroll
-            for (int sx = 0; sx < 2; ++sx)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float p0 = p[8 * sx + 2 * e], p1 = p[8 * sx + 2 * e + 1];
-                    const uint32_t h0 = __float_as_uint(p0) & 0xffff0000u, h1 = __float_as_uint(p1) & 0xffff0000u;
-                    phi[sx].u[e] = __builtin_amdgcn_perm(h1, h0, 0x07060302u);
-                    plo[sx].u[e] = pack_bf16(p0 - __uint_as_float(h0), p1 - __uint_as_float(h1));
-                }
-#pragma unroll
-            for (int ddb = 0; ddb < 4; ++ddb)
-#pragma unroll
-                for (int sx = 0; sx < 2; ++sx) {
-                    const bf16x8 a = lds_read_vt(vtile + (tb * 32 + 16 * sx) * kRowBytes + voff[ddb]);
-                    oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, phi[sx].v, oacc[ddb], 0, 0, 0);
-                    oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, plo[sx].v, oacc[ddb], 0, 0, 0);
-                }
-        }
-    }
-    if (!wave_active) return;
-    const float lrow = lsum + other_half(lsum);
-    const int n_top_row = n_top + __shfl_xor(n_top, 32);
-    const int top_tok_row = max(top_tok, __shfl_xor(top_tok, 32));
-    const size_t prow = rescue_partial_row(lay, bg, n_splits, m_pad, split * lay.fine + sub, slot);
-    if (half == 0) {
-        part_ml[prow * 4 + 0] = lrow;
-        part_ml[prow * 4 + 1] = (float)n_top_row;
-        part_ml[prow * 4 + 2] = __int_as_float(top_tok_row);
-    }
-    float *dst = part_o + prow * kD;
-#pragma unroll
-    for (int ddb = 0; ddb < 4; ++ddb)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-            const int dd = ddb * 32 + 8 * r4 + 4 * half;
-            *(float4 *)(dst + dd) = make_float4(oacc[ddb][4 * r4], oacc[ddb][4 * r4 + 1], oacc[ddb][4 * r4 + 2],
-                                                oacc[ddb][4 * r4 + 3]);
-        }
-}
-
-// One 128-thread block per (list position, KV head); thread = head_dim element.
-__global__ __launch_bounds__(128) void mfma_rescue_combine(const uint16_t *__restrict__ v,
-                                                           const float *__restrict__ part_ml,
-                                                           const float *__restrict__ part_o, int N, int W, int Hq,
-                                                           int Hkv, int ragged, SeqLens lens, int split_len,
-                                                           int n_splits, int m_pad,
-                                                           const int32_t *__restrict__ dom_rows,
-                                                           const int32_t *__restrict__ dom_count,
-                                                           float *__restrict__ row_sum, float *__restrict__ out_f32,
-                                                           uint16_t *__restrict__ out_bf16,
-                                                           float *__restrict__ row_const,
-                                                           float *__restrict__ special) {
-    __shared__ float red[4][2];
-    const int slot = blockIdx.x, bg = blockIdx.y;
-    if (slot >= dom_count[bg]) return;
-    const int b = bg / Hkv, g = bg % Hkv, G = Hq / Hkv;
-    const int len = seq_len_of(lens, ragged, b, N);
-    const int row = dom_rows[(size_t)bg * m_pad + slot];
-    const int dd = threadIdx.x;
-    const int live_splits = (len + split_len - 1) / split_len;
-    const RescueLayout lay = rescue_layout(dom_count[bg], m_pad, split_len);
-    float lrest = 0.f, orest = 0.f, n_top = 0.f;
-    int top_tok = -1;
-    // Sub-ranges are visited in token order, eight at a time with all loads issued before the
-    // first use; a sub-range that starts beyond its split or the sequence was never swept.
-    const int n_sub = live_splits * lay.fine;
-    for (int j0 = 0; j0 < n_sub; j0 += 8) {
-        float4 ml[8];
-        float po[8];
-        bool live[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int j = min(j0 + u, n_sub - 1);
-            const int s = j / lay.fine, sub = j % lay.fine;
-            live[u] = j0 + u < n_sub && s * split_len + sub * lay.sub_len < min((s + 1) * split_len, len);
-            const size_t prow = rescue_partial_row(lay, bg, n_splits, m_pad, j, slot);
-            ml[u] = live[u] ? ((const float4 *)part_ml)[prow] : make_float4(0.f, 0.f, __int_as_float(-1), 0.f);
-            po[u] = live[u] ? part_o[prow * kD + dd] : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            if (!live[u]) continue;
-            lrest += ml[u].x;
-            n_top += ml[u].y;
-            top_tok = max(top_tok, __float_as_int(ml[u].z));
-            orest += po[u];
-        }
-    }
-    if (n_top != 1.0f || top_tok < 0) return;       // cannot happen for a row above kDominantShare; keep the plain results
-    const size_t crow = (size_t)bg * m_pad + row;
-    const size_t lo_plane = (size_t)gridDim.y * m_pad * kD;
-    const float vt = bf16_bits_to_float(v[((size_t)bg * N + top_tok) * kD + dd]);
-    const float ltot = 1.0f + lrest;                 // the top key's own weight is exp(0) = 1
-    const float frac = lrest / ltot;                 // 1 - A_top
-    const float rest = lrest > 0.f ? orest / lrest : 0.f;
-    const float diff = frac * (vt - rest);           // (v_top - o_i)[dd]
-    const float o = vt - diff;
-    const float m_raw = row_const[crow * 4 + 3];
-    const float z = m_raw * kInvSqrtD;               // Z of the (row, top key) pair
-    const float comb = fmaf(z, diff, vt);            // ((1+Z) v_top - Z o_i)[dd]
-    const uint16_t ob = (uint16_t)(__float_as_uint(o) >> 16);
-    const float ohi = bf16_bits_to_float(ob);
-    const uint16_t olo = (uint16_t)(pack_bf16(o - ohi, 0.f) & 0xffffu);
-    const float of = ohi + bf16_bits_to_float(olo);
-    float sums[4] = {of * of, vt * vt, diff * diff, comb * comb};
-#pragma unroll
-    for (int c = 0; c < 4; ++c) {
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) sums[c] += __shfl_xor(sums[c], off);
-        if ((dd & 63) == 0) red[c][dd >> 6] = sums[c];
-    }
-    __syncthreads();
-    const size_t grow = ((size_t)b * Hq + (size_t)g * G) * W + row;
-    out_f32[grow * kD + dd] = o;
-    out_bf16[crow * kD + dd] = minus_twice_bf16(ob);
-    out_bf16[lo_plane + crow * kD + dd] = minus_twice_bf16(olo);
-    if (dd == 0) {
-        const float a = 1.0f / ltot, a2 = a * a;
-        row_sum[grow] = ltot;
-        row_const[crow * 4 + 0] = 2.0f * (m_raw * (kLog2e * kInvSqrtD) + log2f(ltot));
-        row_const[crow * 4 + 1] = red[0][0] + red[0][1];
-        special[crow * 4 + 0] = __int_as_float(top_tok);
-        special[crow * 4 + 1] = a2 * (red[1][0] + red[1][1]);                 // Eq. 4 term of the pair
-        special[crow * 4 + 2] = a2 * z * z * (red[2][0] + red[2][1]);         // Eq. 5 term
-        special[crow * 4 + 3] = a2 * (red[3][0] + red[3][1]);                 // Eq. 6 term (completed square)
-    }
-}
-
-hipError_t launch_rescue(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStream_t stream) {
-    const int BH = a.B * a.Hkv;
-    int32_t *dom_rows = (int32_t *)(base + ws.dom_rows);
-    int32_t *dom_count = dom_rows + (size_t)BH * ws.m_pad;
-    float *part_ml = (float *)(base + ws.part_ml), *part_o = (float *)(base + ws.part_o);
-    // The dynamic-LDS limit of a kernel is sticky: raised once per process (one GPU per process).
-    static const hipError_t lds_ok = hipFuncSetAttribute((const void *)mfma_rescue_sweep, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsTiles);
-    hipError_t e = lds_ok;
-    if (e != hipSuccess) return e;
-    mfma_rescue_sweep<<<dim3(ws.splits, ws.n_chunks, BH), dim3(kThreads), kLdsTiles, stream>>>(
-        (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens,
-        ws.split_len, ws.splits, ws.m_pad, dom_rows, dom_count, (const float *)(base + ws.row_const), part_ml, part_o);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    mfma_rescue_combine<<<dim3(ws.m_pad, BH), dim3(128), 0, stream>>>(
-        (const uint16_t *)a.v, part_ml, part_o, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, ws.split_len, ws.splits,
-        ws.m_pad, dom_rows, dom_count, (float *)(base + ws.row_sum), (float *)(base + ws.out_f32),
-        (uint16_t *)(base + ws.out_bf16), (float *)(base + ws.row_const), (float *)(base + ws.special));
-    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------
@@ -939,7 +904,8 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
                                             int t_begin, int t_end, int last_row, const int *vis_i,
                                             const int *excl_i, const char *kh, const char *vh,
                                             const char *const (&kp)[8], const uint32_t (&kdoff)[4], int wave, int lane,
-                                            bool wave_active, float *part, float *out, size_t variant_stride, bool accumulate) {
+                                            bool wave_active, float *part, float *out, size_t variant_stride, bool accumulate,
+                                            int spec_lo_blk, int spec_hi_blk) {
     constexpr int kNv = kVariant == OBC_ALL ? 3 : 1;
     constexpr bool kDoV = kVariant == OBC_VALUE || kVariant == OBC_ALL;
     constexpr bool kDoK = kVariant == OBC_KEY || kVariant == OBC_ALL;
@@ -984,7 +950,17 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
                 vo = __builtin_amdgcn_mfma_f32_32x32x16_bf16(R.olo[kk], vb, vo, 0, 0, 0);
             }
         }
-        vv += other_half(vv);                                          // ||v_p||^2 of this lane's token
+        vv += __shfl_xor(vv, 32);                                         // ||v_p||^2 of this lane's token
+        if (!kMasked && kNeedVO && n >= spec_lo_blk && n <= spec_hi_blk) {      // uniform, rare
+            // This fully visible block may hold a (row, key) pair that is scored separately: such a pair gets a
+            // logit so low that its weight is exactly 0 (and low enough only for that: every product below stays finite).
+            const int tokx = t_begin + n * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int i = wave * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (tokx == excl_i[i]) z[r] = -1e15f;
+            }
+        }
         // ---- vector ALUs ----
         // vo holds -2 v_p.o^_i (the stationary pieces are stored pre-scaled by -2, an exact
         // scaling), so with w = ||v_p - o^_i||^2 = (||v_p||^2 + ||o^_i||^2) + vo:
@@ -1014,9 +990,9 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
             }
         }
         if (kDoV || kVariant == OBC_VATP) acc_v *= vv;                 // ||v_p||^2, or ||v_p||_1 for the l1 form
-        if (kDoV || kDoA) acc_v += other_half(acc_v);
-        if (kDoK) { acc_k += other_half(acc_k); acc_k = fmaxf(acc_k, 0.f); }
-        if (kDoJ) { acc_j += other_half(acc_j); acc_j = fmaxf(acc_j, 0.f); }
+        if (kDoV || kDoA) acc_v += __shfl_xor(acc_v, 32);
+        if (kDoK) { acc_k += __shfl_xor(acc_k, 32); acc_k = fmaxf(acc_k, 0.f); }
+        if (kDoJ) { acc_j += __shfl_xor(acc_j, 32); acc_j = fmaxf(acc_j, 0.f); }
     }
     if (half == 0) {
         float *pw = part + ((kSlot * 4 + wave) * kNv) * 64 + kBlk * 32 + lane;
@@ -1126,6 +1102,10 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r) { settle(R.c_m2[r]); settle(R.c_oo[r]); }
+    // First and last block (of 32 tokens, counted from t_begin) that hold a separately scored (row, key) pair.
+    __shared__ int spec_lo, spec_hi;
+    if (threadIdx.x == 0) { spec_lo = 0x7fffffff; spec_hi = -1; }
+    __syncthreads();
     int mine_special = 0;
     if (threadIdx.x < 128) {
         const int i = chunk * 128 + threadIdx.x;
@@ -1133,6 +1113,10 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
         const int ex = (kNeedVO && i < m_pad) ? __float_as_int(special[(cbase + i) * 4 + 0]) : -1;
         excl_s[threadIdx.x] = __int_as_float(ex);
         mine_special = ex >= t_begin && ex < t_end;
+        if (mine_special) {
+            atomicMin(&spec_lo, (ex - t_begin) >> 5);
+            atomicMax(&spec_hi, (ex - t_begin) >> 5);
+        }
     }
     const int *vis_i = (const int *)vis_s, *excl_i = (const int *)excl_s;
     // Uniform: some (row, key) pair of this chunk and token range is scored separately.
@@ -1140,9 +1124,12 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
 
     const int n_blk = (t_end - t_begin + 31) / 32;
     const int n_total = (n_blk + 3) & ~3;
-    int n_plain = (vis_min + 1 - t_begin) / 32;
-    n_plain = has_special ? 0 : (max(0, min(n_plain, n_blk)) & ~3);
-#define OBC_S2_ARGS smem, lds0, n, n_blk, t_begin, t_end, len - 1, vis_i, excl_i, kh, vh, kp, kdoff, wave, lane, wave_active, part, out, variant_stride, accumulate
+    int n_plain = (vis_min + 1 - t_begin) / 32;       // leading blocks every row of this wave sees in full
+    n_plain = max(0, min(n_plain, n_blk)) & ~3;
+    // Blocks m_lo .. m_hi span the separately scored pairs of this range (none: an empty span).
+    const int m_lo = has_special ? __builtin_amdgcn_readfirstlane(spec_lo) : 1;
+    const int m_hi = has_special ? __builtin_amdgcn_readfirstlane(spec_hi) : 0;
+#define OBC_S2_ARGS smem, lds0, n, n_blk, t_begin, t_end, len - 1, vis_i, excl_i, kh, vh, kp, kdoff, wave, lane, wave_active, part, out, variant_stride, accumulate, m_lo, m_hi
     int n = 0;
     for (; n < n_plain; n += 4) {
         sweep2_step<0, false, kVariant>(R, OBC_S2_ARGS); ++n;
@@ -1164,17 +1151,36 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
         for (int t = t_end + threadIdx.x; t < t_stop; t += kThreads)
 #pragma unroll
             for (int c = 0; c < kNv; ++c) out[c * variant_stride + t] = 0.f;
-    if (has_special) {      // add the separately scored pairs, in row order, by one thread
+    if (has_special) {
+        // Add the separately scored pairs: staged in LDS (the tiles are done with), then summed by one
+        // thread in row order; consecutive rows that share their key (a sink, typically) cost one update.
+        wait_async_loads();
+        __syncthreads();
+        float4 *staged = (float4 *)smem;
+        if (threadIdx.x < 128) {
+            const int i = chunk * 128 + threadIdx.x;
+            staged[threadIdx.x] = i < m_pad ? ((const float4 *)special)[cbase + i] : make_float4(__int_as_float(-1), 0.f, 0.f, 0.f);
+        }
         __syncthreads();
         if (threadIdx.x == 0) {
-            for (int i = 0; i < 128; ++i) {
-                const int ex = excl_i[i];
-                if (ex < t_begin || ex >= t_end) continue;
-                const float *sp = special + (cbase + chunk * 128 + i) * 4;
-                int c = 0;
-                if (kVariant == OBC_VALUE || kVariant == OBC_ALL) out[(c++) * variant_stride + ex] += sp[1];
-                if (kVariant == OBC_KEY || kVariant == OBC_ALL) out[(c++) * variant_stride + ex] += sp[2];
-                if (kVariant == OBC_JOINT || kVariant == OBC_ALL) out[(c++) * variant_stride + ex] += sp[3];
+            int cur = -1;
+            float acc[3] = {0.f, 0.f, 0.f};
+            for (int i = 0; i <= 128; ++i) {
+                const float4 sp = i < 128 ? staged[i] : make_float4(__int_as_float(-2), 0.f, 0.f, 0.f);
+                const int ex = __float_as_int(sp.x);
+                const bool mine = ex >= t_begin && ex < t_end;
+                if (i < 128 && !mine) continue;
+                if (ex != cur) {
+                    if (cur >= 0) {
+                        int c = 0;
+                        if (kVariant == OBC_VALUE || kVariant == OBC_ALL) out[(c++) * variant_stride + cur] += acc[0];
+                        if (kVariant == OBC_KEY || kVariant == OBC_ALL) out[(c++) * variant_stride + cur] += acc[1];
+                        if (kVariant == OBC_JOINT || kVariant == OBC_ALL) out[(c++) * variant_stride + cur] += acc[2];
+                    }
+                    cur = i < 128 ? ex : -1;
+                    acc[0] = acc[1] = acc[2] = 0.f;
+                }
+                acc[0] += sp.y; acc[1] += sp.z; acc[2] += sp.w;
             }
         }
     }
@@ -1246,7 +1252,6 @@ void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWo
     ws->row_const = *off; *off = align_up(*off + rows * 4 * sizeof(float), 256);
     ws->part_ml = *off;   *off = align_up(*off + rows * ws->splits * 4 * sizeof(float), 256);
     ws->special = *off;   *off = align_up(*off + rows * 4 * sizeof(float), 256);
-    ws->dom_rows = *off;  *off = align_up(*off + (rows + BH) * sizeof(int32_t), 256);
     ws->part_o = *off;    *off = align_up(*off + rows * ws->splits * d * sizeof(float), 256);
     ws->planes = *off;
     if (ws->n_chunks > 1) *off = align_up(*off + (size_t)ws->n_chunks * nv * BH * N * sizeof(float), 256);
@@ -1255,8 +1260,6 @@ void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWo
 hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStream_t stream) {
     const bool need_o = a.variant == OBC_KEY || a.variant == OBC_JOINT || a.variant == OBC_ALL;
     float *part_ml = (float *)(base + ws.part_ml), *part_o = (float *)(base + ws.part_o);
-    int32_t *dom_rows = (int32_t *)(base + ws.dom_rows);
-    int32_t *dom_count = dom_rows + (size_t)a.B * a.Hkv * ws.m_pad;
     hipError_t e = hipSuccess;
     if (a.stage_mask & OBC_STAGE_SWEEP1) {
         const size_t lds = kLdsTiles;
@@ -1268,26 +1271,27 @@ hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char 
         if (need_o)
             mfma_sweep1<true><<<grid, dim3(kThreads), lds, stream>>>(
                 (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged,
-                a.lens, ws.split_len, ws.splits, ws.m_pad, part_ml, part_o, dom_count);
+                a.lens, ws.split_len, ws.splits, ws.m_pad, part_ml, part_o);
         else
             mfma_sweep1<false><<<grid, dim3(kThreads), lds, stream>>>(
                 (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged,
-                a.lens, ws.split_len, ws.splits, ws.m_pad, part_ml, part_o, dom_count);
+                a.lens, ws.split_len, ws.splits, ws.m_pad, part_ml, part_o);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     if (a.stage_mask & OBC_STAGE_COMBINE) {
-        mfma_combine<<<dim3(ws.m_pad, a.B * a.Hkv), dim3(128), 0, stream>>>(
-            part_ml, part_o, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, ws.split_len, ws.splits, ws.m_pad,
-            need_o ? 1 : 0, (float *)(base + ws.row_max), (float *)(base + ws.row_sum),
-            (float *)(base + ws.out_f32), (uint16_t *)(base + ws.out_bf16), (float *)(base + ws.row_const),
-            (float *)(base + ws.special), dom_rows, dom_count);
+        const dim3 grid(ws.m_pad, a.B * a.Hkv);
+        if (need_o)
+            mfma_combine_hold<<<grid, dim3(128), 0, stream>>>(
+                (const uint16_t *)a.v, part_ml, part_o, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, ws.split_len,
+                ws.splits, ws.m_pad, (uint16_t *)(base + ws.out_bf16), (float *)(base + ws.row_const),
+                (float *)(base + ws.special));
+        else
+            mfma_combine<<<grid, dim3(128), 0, stream>>>(
+                part_ml, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, ws.split_len, ws.splits, ws.m_pad,
+                (uint16_t *)(base + ws.out_bf16), (float *)(base + ws.row_const), (float *)(base + ws.special));
         e = hipGetLastError();
         if (e != hipSuccess) return e;
-        if (need_o) {
-            e = launch_rescue(a, ws, base, stream);
-            if (e != hipSuccess) return e;
-        }
     }
     if (!(a.stage_mask & OBC_STAGE_SWEEP2)) return hipSuccess;
     switch (a.variant) {
