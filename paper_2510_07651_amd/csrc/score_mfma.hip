@@ -359,14 +359,6 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
     if (kNeedO)
         block_load_async<kRot4>(vh, t_begin + (n + 2) * 32, last_row, lds0 + (4 + ((PH + 2) & 3)) * kBlkBytes, wave, lane, vdoff);
     if (!wave_active) return;
-    // The running max moved in the previous step: bring the accumulated O^T (blocks <= n-2)
-    // to the new reference before block n-1, whose weights already use it, is added.
-    if (kNeedO && R.rescale) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) R.oacc[i][r] *= R.alpha;
-    }
 
     // ---- matrix cores: block n+1 ----
     f32x16 s_next = zero16();
@@ -391,12 +383,21 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
     mx = fmaxf(mx, s[15]);
     mx = halves_max(mx);
     if (kNeedO) {
-        // Rows whose block maximum clears their running maximum by the margin take the block's first key of
-        // that logit as their candidate: its logit becomes -inf before the weights are formed, so it never
-        // enters this block's P or sum, and the previous candidate is parked (or, with the list full, added
-        // back on the spot).  (-inf + margin = -inf: a row's first visible key always is a candidate.)
+        // Rows whose block maximum clears their running maximum (and the block's other keys) by the margin
+        // take the block's first key of that logit as their candidate: its logit becomes -inf before the
+        // weights are formed, so it never enters this block's P or sum, and the previous candidate is parked
+        // (or, with the list full, added back on the spot).  (-inf + margin = -inf: in a row's first visible
+        // block only the block's other keys decide.)
         const float m_true_before = R.m_true;
-        if (__any(mx > m_true_before + kCandMargin)) {                 // uniform
+        if (R.rescale || __any(mx > m_true_before + kCandMargin)) {    // uniform; one branch for both rare events
+            // The running max moved in the previous step: bring the accumulated O^T (blocks <= n-2)
+            // to the new reference before block n-1, whose weights already use it, is added.
+            if (R.rescale) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) R.oacc[i][r] *= R.alpha;
+            }
             if (mx > m_true_before + kCandMargin) {
                 uint32_t hit = 0;
 #pragma unroll
@@ -408,19 +409,26 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
                 both_halves(__int_as_float(off_own), off_lower, off_upper);      // (bits only)
                 const int off_first = min(__float_as_int(off_lower), __float_as_int(off_upper));
                 const int rc = off_own == off_first ? rc_own : -1;              // its register, if in this lane
+                // It must clear the other keys of its own block by the margin as well.
+                float others = -INFINITY;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) s[r] = r == rc ? -INFINITY : s[r];
-                if (R.cand_tok >= 0) {                                 // the previous candidate is an ordinary key after all
-                    if (R.n_ev < kEvents) {
-                        events[R.n_ev] = make_int2(R.cand_tok, __float_as_int(R.cand_val));
-                        R.n_ev += 1;
-                    } else {
-                        // (sum and O^T both stand at the current reference: the owed rescale was applied above)
-                        add_back(R, vh, R.cand_tok, R.cand_val, R.m_ref, R.m_ref, half);
+                for (int r = 0; r < 16; ++r) others = fmaxf(others, r == rc ? -INFINITY : s[r]);
+                others = halves_max(others);
+                if (mx > others + kCandMargin) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) s[r] = r == rc ? -INFINITY : s[r];
+                    if (R.cand_tok >= 0) {                             // the previous candidate is an ordinary key after all
+                        if (R.n_ev < kEvents) {
+                            events[R.n_ev] = make_int2(R.cand_tok, __float_as_int(R.cand_val));
+                            R.n_ev += 1;
+                        } else {
+                            // (sum and O^T both stand at the current reference: the owed rescale was applied above)
+                            add_back(R, vh, R.cand_tok, R.cand_val, R.m_ref, R.m_ref, half);
+                        }
                     }
+                    R.cand_tok = t_begin + n * 32 + off_first;
+                    R.cand_val = mx;
                 }
-                R.cand_tok = t_begin + n * 32 + off_first;
-                R.cand_val = mx;
             }
         }
         // ---- matrix cores: block n-1 ----
