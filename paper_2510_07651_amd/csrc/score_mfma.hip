@@ -216,20 +216,19 @@ __device__ __forceinline__ void both_halves(float x, float &lower, float &upper)
 }
 __device__ __forceinline__ float halves_sum(float x) { float a, b; both_halves(x, a, b); return a + b; }
 __device__ __forceinline__ float halves_max(float x) { float a, b; both_halves(x, a, b); return fmaxf(a, b); }
-// Sum over the 64 lanes of a wave, the same bits in every lane.  Lane pairings inside a row of 16 through the
-// data-parallel-primitive lane controls (neighbours, neighbouring pairs, mirror image inside 8 and inside 16:
-// register to register), then the row next door and the other half of the wave.  Call with every lane active.
+// Sum over the 32 lanes of each half of a wave, the same bits in each of them.  Lane pairings inside a row of
+// 16 through the data-parallel-primitive lane controls (neighbours, neighbouring pairs, mirror image inside 8
+// and inside 16: register to register), then the row next door.  Call with every lane active.
 template <int kCtrl>
 __device__ __forceinline__ float dpp_pair_sum(float x) {
     return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), kCtrl, 0xf, 0xf, false));
 }
-__device__ __forceinline__ float wave_sum(float x) {
+__device__ __forceinline__ float row_sum32(float x) {      // over each half of the wave (32 lanes)
     x = dpp_pair_sum<0xB1>(x);
     x = dpp_pair_sum<0x4E>(x);
     x = dpp_pair_sum<0x141>(x);
     x = dpp_pair_sum<0x140>(x);
-    x += __shfl_xor(x, 16);
-    return halves_sum(x);
+    return x + __shfl_xor(x, 16);
 }
 __device__ __forceinline__ f32x16 zero16() {
     f32x16 z;
@@ -724,6 +723,7 @@ __global__ __launch_bounds__(128) void mfma_combine(const float *__restrict__ pa
 //     v_cand - o_i = l' / (w + l') * (v_cand - O' / l'),      o_i = v_cand - (v_cand - o_i)
 // without cancellation however much of the row's attention the candidate holds.  A candidate that
 // holds a large share is scored here from these (`special`) and skipped by the second sweep.
+// Grid: x = group of four padded rows, y = (b, KV head); 32 lanes per row, four head_dim elements per lane.
 __global__ __launch_bounds__(128) void mfma_combine_hold(const uint16_t *__restrict__ v,
                                                          const float *__restrict__ part_ml,
                                                          const float *__restrict__ part_o, int N, int W, int Hq,
@@ -731,25 +731,13 @@ __global__ __launch_bounds__(128) void mfma_combine_hold(const uint16_t *__restr
                                                          int n_splits, int m_pad, uint16_t *__restrict__ out_bf16,
                                                          float *__restrict__ row_const,
                                                          float *__restrict__ special) {
-    __shared__ float red[4][2];
-    const int row = blockIdx.x, bg = blockIdx.y;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 5), bg = blockIdx.y;
     const int b = bg / Hkv, G = Hq / Hkv, M = G * W;
     const int len = seq_len_of(lens, ragged, b, N);
-    const int dd = threadIdx.x;
+    const int sub = threadIdx.x & 31, dd = sub * 4;   // this lane's elements dd .. dd + 3
     const size_t crow = (size_t)bg * m_pad + row;
     const size_t lo_plane = (size_t)gridDim.y * m_pad * kD;
-    if (row >= M) {                                   // padded row: weightless in the second sweep
-        out_bf16[crow * kD + dd] = 0;
-        out_bf16[lo_plane + crow * kD + dd] = 0;
-        if (dd == 0) {
-            row_const[crow * 4 + 0] = 1e30f;
-            row_const[crow * 4 + 1] = 0.f;
-            row_const[crow * 4 + 2] = __int_as_float(-1);
-            row_const[crow * 4 + 3] = 0.f;
-            special[crow * 4 + 0] = __int_as_float(-1);
-        }
-        return;
-    }
+    const bool live = row < M;                        // the same for the 32 lanes of a row
     const int live_splits = (len + split_len - 1) / split_len;
     const float c2 = kLog2e * kInvSqrtD;
     const uint16_t *vg = v + (size_t)bg * N * kD;
@@ -758,13 +746,12 @@ __global__ __launch_bounds__(128) void mfma_combine_hold(const uint16_t *__restr
     // The first 16 splits' records and sums are fetched in one go and stay in registers.
     float T = -INFINITY, c_val = -INFINITY;
     int c_tok = -1, s_star = -1;
-    float4 ml[16];
-    float po[16];
+    float4 ml[16], po[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
         const size_t prow = ((size_t)bg * n_splits + min(j, live_splits - 1)) * m_pad + row;
         ml[j] = ((const float4 *)part_ml)[prow];
-        po[j] = part_o[prow * kD + dd];
+        po[j] = *(const float4 *)(part_o + prow * kD + dd);
     }
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
@@ -786,34 +773,41 @@ __global__ __launch_bounds__(128) void mfma_combine_hold(const uint16_t *__restr
             if (tok >= 0 && mm[j].z > c_val) { c_val = mm[j].z; c_tok = tok; s_star = s0 + j; }
         }
     }
-    const float vt = c_tok >= 0 ? bf16_bits_to_float(vg[(size_t)c_tok * kD + dd]) : 0.f;
-    float l = 0.f, o = 0.f;
+    if (!live) { c_tok = -1; s_star = -1; }           // padded rows: zero queries, nothing of theirs is used
+    const uint2 vt_bits = c_tok >= 0 ? *(const uint2 *)(vg + (size_t)c_tok * kD + dd) : make_uint2(0u, 0u);
+    float l = 0.f, o[4] = {0.f, 0.f, 0.f, 0.f};
     for (int s0 = 0; s0 < live_splits; s0 += 16) {
-        float vo[16];
+        uint2 vo[16];
         if (s0 > 0) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) {         // (the records are in cache from the pass above)
                 const size_t prow = ((size_t)bg * n_splits + min(s0 + j, live_splits - 1)) * m_pad + row;
                 ml[j] = ((const float4 *)part_ml)[prow];
-                po[j] = part_o[prow * kD + dd];
+                po[j] = *(const float4 *)(part_o + prow * kD + dd);
             }
         }
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int tok = __float_as_int(ml[j].w);
-            const bool back = s0 + j < live_splits && s0 + j != s_star && tok >= 0;
-            vo[j] = back ? bf16_bits_to_float(vg[(size_t)tok * kD + dd]) : 0.f;
+            const bool back = live && s0 + j < live_splits && s0 + j != s_star && tok >= 0;
+            vo[j] = back ? *(const uint2 *)(vg + (size_t)tok * kD + dd) : make_uint2(0u, 0u);
         }
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             if (s0 + j >= live_splits) continue;
             const float w = ml[j].x == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((ml[j].x - T) * c2);
             l = fmaf(w, ml[j].y, l);
-            o = fmaf(w, po[j], o);
-            if (s0 + j != s_star && __float_as_int(ml[j].w) >= 0) {   // this split's candidate is an ordinary key
+            o[0] = fmaf(w, po[j].x, o[0]);
+            o[1] = fmaf(w, po[j].y, o[1]);
+            o[2] = fmaf(w, po[j].z, o[2]);
+            o[3] = fmaf(w, po[j].w, o[3]);
+            if (live && s0 + j != s_star && __float_as_int(ml[j].w) >= 0) {   // this split's candidate is an ordinary key
                 const float wc = __builtin_amdgcn_exp2f((ml[j].z - T) * c2);
                 l += wc;
-                o = fmaf(wc, vo[j], o);
+                o[0] = fmaf(wc, __uint_as_float(vo[j].x << 16), o[0]);
+                o[1] = fmaf(wc, __uint_as_float(vo[j].x & 0xffff0000u), o[1]);
+                o[2] = fmaf(wc, __uint_as_float(vo[j].y << 16), o[2]);
+                o[3] = fmaf(wc, __uint_as_float(vo[j].y & 0xffff0000u), o[3]);
             }
         }
     }
@@ -821,40 +815,59 @@ __global__ __launch_bounds__(128) void mfma_combine_hold(const uint16_t *__restr
     const float wc = c_tok >= 0 ? __builtin_amdgcn_exp2f((c_val - T) * c2) : 0.f;
     const float ltot = wc + l;
     const float inv = 1.0f / ltot;
-    const float rest = l > 0.f ? o / l : 0.f;
-    const float diff = (l * inv) * (vt - rest);      // (v_cand - o_i)[dd]
-    const float oi = vt - diff;
+    const float inv_l = l > 0.f ? 1.0f / l : 0.f;
     const float z = c_val * kInvSqrtD;               // Z of the (row, candidate) pair
-    const float comb = fmaf(z, diff, vt);            // ((1+Z) v_cand - Z o_i)[dd]
-    const uint16_t ob = (uint16_t)(__float_as_uint(oi) >> 16);
-    const float ohi = bf16_bits_to_float(ob);
-    const uint16_t olo = (uint16_t)(pack_bf16(oi - ohi, 0.f) & 0xffffu);
-    const float of = ohi + bf16_bits_to_float(olo);
-    // A candidate with a small share is scored by the second sweep like any other key (its o_i is exact either
-    // way); one that may dominate is scored here and skipped there.  (Uniform: every thread holds the same sums.)
-    const float a = wc * inv;
-    const bool separate = a >= kSeparateShare;
-    const float oo = wave_sum(of * of);
-    if ((dd & 63) == 0) red[0][dd >> 6] = oo;
-    if (separate) {
-        const float s1 = wave_sum(vt * vt), s2 = wave_sum(diff * diff), s3 = wave_sum(comb * comb);
-        if ((dd & 63) == 0) { red[1][dd >> 6] = s1; red[2][dd >> 6] = s2; red[3][dd >> 6] = s3; }
+    const float vt[4] = {__uint_as_float(vt_bits.x << 16), __uint_as_float(vt_bits.x & 0xffff0000u),
+                         __uint_as_float(vt_bits.y << 16), __uint_as_float(vt_bits.y & 0xffff0000u)};
+    uint16_t ob[4], olo[4];
+    float s_oo = 0.f, s_vv = 0.f, s_dd = 0.f, s_cc = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float diff = (l * inv) * (vt[e] - o[e] * inv_l);     // (v_cand - o_i)[dd + e]
+        const float oi = vt[e] - diff;
+        const float comb = fmaf(z, diff, vt[e]);                   // ((1+Z) v_cand - Z o_i)[dd + e]
+        // o^ = hi + lo, the pair of bf16 pieces the second sweep feeds to the matrix cores.
+        ob[e] = (uint16_t)(__float_as_uint(oi) >> 16);
+        const float ohi = bf16_bits_to_float(ob[e]);
+        olo[e] = (uint16_t)(pack_bf16(oi - ohi, 0.f) & 0xffffu);
+        const float of = ohi + bf16_bits_to_float(olo[e]);
+        s_oo = fmaf(of, of, s_oo);
+        s_vv = fmaf(vt[e], vt[e], s_vv);
+        s_dd = fmaf(diff, diff, s_dd);
+        s_cc = fmaf(comb, comb, s_cc);
     }
-    __syncthreads();
-    out_bf16[crow * kD + dd] = minus_twice_bf16(ob);
-    out_bf16[lo_plane + crow * kD + dd] = minus_twice_bf16(olo);
-    if (dd == 0) {
-        const float a2 = a * a;
-        row_const[crow * 4 + 0] = 2.0f * (T * c2 + log2f(ltot));   // A_ip^2 = exp2(2 log2e Z_ip - this)
-        row_const[crow * 4 + 1] = red[0][0] + red[0][1];           // ||o^_i||^2
-        row_const[crow * 4 + 2] = __int_as_float(len - W + (row % W));
+    // A candidate with a small share is scored by the second sweep like any other key (its o_i is exact either
+    // way); one that may dominate is scored here and skipped there.
+    const float a = wc * inv;
+    const bool separate = live && a >= kSeparateShare;
+    s_oo = row_sum32(s_oo);
+    if (__any(separate)) { s_vv = row_sum32(s_vv); s_dd = row_sum32(s_dd); s_cc = row_sum32(s_cc); }
+    uint2 hi_bits, lo_bits;
+    hi_bits.x = live ? (uint32_t)minus_twice_bf16(ob[0]) | ((uint32_t)minus_twice_bf16(ob[1]) << 16) : 0u;
+    hi_bits.y = live ? (uint32_t)minus_twice_bf16(ob[2]) | ((uint32_t)minus_twice_bf16(ob[3]) << 16) : 0u;
+    lo_bits.x = live ? (uint32_t)minus_twice_bf16(olo[0]) | ((uint32_t)minus_twice_bf16(olo[1]) << 16) : 0u;
+    lo_bits.y = live ? (uint32_t)minus_twice_bf16(olo[2]) | ((uint32_t)minus_twice_bf16(olo[3]) << 16) : 0u;
+    *(uint2 *)(out_bf16 + crow * kD + dd) = hi_bits;
+    *(uint2 *)(out_bf16 + lo_plane + crow * kD + dd) = lo_bits;
+    if (sub != 0) return;
+    if (!live) {                                      // padded row: weightless in the second sweep
+        row_const[crow * 4 + 0] = 1e30f;
+        row_const[crow * 4 + 1] = 0.f;
+        row_const[crow * 4 + 2] = __int_as_float(-1);
         row_const[crow * 4 + 3] = 0.f;
-        special[crow * 4 + 0] = __int_as_float(separate ? c_tok : -1);
-        if (separate) {
-            special[crow * 4 + 1] = a2 * (red[1][0] + red[1][1]);             // Eq. 4 term of the pair
-            special[crow * 4 + 2] = a2 * z * z * (red[2][0] + red[2][1]);     // Eq. 5 term
-            special[crow * 4 + 3] = a2 * (red[3][0] + red[3][1]);             // Eq. 6 term (completed square)
-        }
+        special[crow * 4 + 0] = __int_as_float(-1);
+        return;
+    }
+    const float a2 = a * a;
+    row_const[crow * 4 + 0] = 2.0f * (T * c2 + log2f(ltot));   // A_ip^2 = exp2(2 log2e Z_ip - this)
+    row_const[crow * 4 + 1] = s_oo;                            // ||o^_i||^2
+    row_const[crow * 4 + 2] = __int_as_float(len - W + (row % W));
+    row_const[crow * 4 + 3] = 0.f;
+    special[crow * 4 + 0] = __int_as_float(separate ? c_tok : -1);
+    if (separate) {
+        special[crow * 4 + 1] = a2 * s_vv;             // Eq. 4 term of the pair
+        special[crow * 4 + 2] = a2 * z * z * s_dd;     // Eq. 5 term
+        special[crow * 4 + 3] = a2 * s_cc;             // Eq. 6 term (completed square)
     }
 }
 
@@ -1066,6 +1079,15 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
     tile_load_async<kXor16>(kh, t_begin, len - 1, lds0 + kLdsK0, wave, lane, kdoff);
     if (kVariant != OBC_ATTN) tile_load_async<kXor16>(vh, t_begin, len - 1, lds0 + kLdsV0, wave, lane, kdoff);
 
+    // (fetched with the stationary operands below, in one memory round trip; used after them)
+    float my_vis = __int_as_float(-1);
+    int my_excl = -1;
+    if (threadIdx.x < 128) {
+        const int i = chunk * 128 + threadIdx.x;
+        if (i < m_pad) my_vis = row_const[(cbase + i) * 4 + 2];
+        if (kNeedVO && i < m_pad) my_excl = __float_as_int(special[(cbase + i) * 4 + 0]);
+    }
+
     int koff[8];
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) koff[kk] = row_piece_offset(lane, kk);
@@ -1116,9 +1138,8 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
     __syncthreads();
     int mine_special = 0;
     if (threadIdx.x < 128) {
-        const int i = chunk * 128 + threadIdx.x;
-        vis_s[threadIdx.x] = i < m_pad ? row_const[(cbase + i) * 4 + 2] : __int_as_float(-1);
-        const int ex = (kNeedVO && i < m_pad) ? __float_as_int(special[(cbase + i) * 4 + 0]) : -1;
+        const int ex = my_excl;
+        vis_s[threadIdx.x] = my_vis;
         excl_s[threadIdx.x] = __int_as_float(ex);
         mine_special = ex >= t_begin && ex < t_end;
         if (mine_special) {
@@ -1290,7 +1311,7 @@ hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char 
     if (a.stage_mask & OBC_STAGE_COMBINE) {
         const dim3 grid(ws.m_pad, a.B * a.Hkv);
         if (need_o)
-            mfma_combine_hold<<<grid, dim3(128), 0, stream>>>(
+            mfma_combine_hold<<<dim3(ws.m_pad / 4, a.B * a.Hkv), dim3(128), 0, stream>>>(      // (m_pad: a multiple of 32)
                 (const uint16_t *)a.v, part_ml, part_o, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, ws.split_len,
                 ws.splits, ws.m_pad, (uint16_t *)(base + ws.out_bf16), (float *)(base + ws.row_const),
                 (float *)(base + ws.special));
