@@ -47,11 +47,17 @@ __device__ __forceinline__ uint32_t order_key(float f) {
 constexpr int kBins = 2048;
 constexpr int kMaxRadius = 7;                           // largest pooling window: 15 scores
 
+constexpr int kMaxRegChunks = 16;                       // chunks a block can keep in registers (64K scores)
+
 struct SelectShared {
     int hist[kBins];
     int wave_tot[kSelWaves];
     uint32_t sel_digit;
     int sel_remaining;
+    // ordered emission of a register-resident head: per (chunk, wave) the packed counts, then the
+    // numbers of greater / equal keys that come before that (chunk, wave)
+    int cw_tot[kMaxRegChunks * kSelWaves];
+    int cw_gt[kMaxRegChunks * kSelWaves], cw_eq[kMaxRegChunks * kSelWaves];
 };
 
 __device__ __forceinline__ void histogram_add(int *hist, uint32_t digit, bool active) {
@@ -135,6 +141,83 @@ __device__ __forceinline__ void emit_chunk(SelectShared &sh, const uint32_t (&ke
     gt_base += total >> 16;
     eq_base += total & 0xffff;
     __syncthreads();
+}
+
+// Ordered emission of a head whose keys all sit in registers: the same positions as emit_chunk chunk after
+// chunk, with three barriers in all.  Every wave scans its 256 keys of every chunk; the first wave then
+// scans the (chunk, wave) totals in emission order; every thread places its keys.
+template <int kRegChunks>
+__device__ __forceinline__ void emit_resident(SelectShared &sh, const uint32_t (&keys)[kRegChunks][kItems], int n_chunks,
+                                              int len, uint32_t thr, int need_eq, int budget, int32_t *out) {
+    static_assert(kRegChunks <= kMaxRegChunks, "cw_tot is sized for kMaxRegChunks chunks");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int before[kRegChunks];                     // packed counts: low 16 bits #equal, high 16 bits #greater (<= 256 per wave)
+#pragma unroll
+    for (int c = 0; c < kRegChunks; ++c) {
+        // Counts over the lower lanes and over the wave from the lane masks of the comparisons (no shuffles).
+        const int i0 = c * kChunk + tid * kItems;
+        int gt_lower = 0, eq_lower = 0, gt_wave = 0, eq_wave = 0;
+#pragma unroll
+        for (int e = 0; e < kItems; ++e) {
+            const bool in = c < n_chunks && i0 + e < len;
+            const unsigned long long mg = __ballot(in && keys[c][e] > thr), me = __ballot(in && keys[c][e] == thr);
+            gt_lower += __builtin_amdgcn_mbcnt_hi((uint32_t)(mg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mg, 0));
+            eq_lower += __builtin_amdgcn_mbcnt_hi((uint32_t)(me >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)me, 0));
+            gt_wave += __popcll(mg);
+            eq_wave += __popcll(me);
+        }
+        if (lane == 0) sh.cw_tot[c * kSelWaves + wave] = (gt_wave << 16) | eq_wave;
+        before[c] = (gt_lower << 16) | eq_lower;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        // entries in emission order: j = chunk * kSelWaves + wave; lane l owns kPer consecutive ones
+        constexpr int kPer = kRegChunks * kSelWaves / 64 > 0 ? kRegChunks * kSelWaves / 64 : 1;
+        constexpr int kEntries = kRegChunks * kSelWaves;
+        int gt[kPer], eq[kPer], gsum = 0, esum = 0;
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int j = lane * kPer + u;
+            const int t = j < kEntries ? sh.cw_tot[j] : 0;
+            gt[u] = t >> 16; eq[u] = t & 0xffff;
+            gsum += gt[u]; esum += eq[u];
+        }
+        int ginc = gsum, einc = esum;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int tg = __shfl_up(ginc, off), te = __shfl_up(einc, off);
+            if (lane >= off) { ginc += tg; einc += te; }
+        }
+        int g = ginc - gsum, q = einc - esum;       // exclusive
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int j = lane * kPer + u;
+            if (j < kEntries) { sh.cw_gt[j] = g; sh.cw_eq[j] = q; }
+            g += gt[u]; q += eq[u];
+        }
+    }
+    __syncthreads();
+    // (the comparisons are taken again rather than kept: 128 lane masks would not fit the scalar registers)
+    uint32_t thr_again = thr;
+    asm volatile("" : "+v"(thr_again));
+#pragma unroll
+    for (int c = 0; c < kRegChunks; ++c) {
+        if (c >= n_chunks) continue;              // uniform
+        const int i0 = c * kChunk + tid * kItems;
+        int gt_before = sh.cw_gt[c * kSelWaves + wave] + (before[c] >> 16);
+        int eq_before = sh.cw_eq[c * kSelWaves + wave] + (before[c] & 0xffff);
+#pragma unroll
+        for (int e = 0; e < kItems; ++e) {
+            const bool in = i0 + e < len;
+            const bool gt = in && keys[c][e] > thr_again, eq = in && keys[c][e] == thr_again;
+            if (gt || (eq && eq_before < need_eq)) {
+                const int pos = gt_before + min(eq_before, need_eq);
+                if (pos < budget) out[pos] = i0 + e;          // always true; guards the store
+            }
+            gt_before += gt ? 1 : 0;
+            eq_before += eq ? 1 : 0;
+        }
+    }
 }
 
 // Keys of chunks c0 .. c0 + kRegChunks - 1 of one head (128-bit loads where possible).
@@ -253,10 +336,7 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
     // ---- ordered sweep ----
     int gt_base = 0, eq_base = 0;
     if constexpr (kResident) {
-#pragma unroll
-        for (int c = 0; c < kRegChunks; ++c)
-            if (c < n_chunks)
-                emit_chunk(sh, keys[c], c * kChunk + tid * kItems, len, thr, need_eq, budget, gt_base, eq_base, out);
+        emit_resident<kRegChunks>(sh, keys, n_chunks, len, thr, need_eq, budget, out);
     } else {
         for (int c0 = 0; c0 < n_chunks; c0 += kRegChunks) {
             load_batch<kRegChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff, radius, keys_in != 0);
