@@ -22,6 +22,11 @@
  *   - Nothing here allocates, frees or synchronises.  All work is enqueued on
  *     `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).
  *     Outputs are valid once that stream has reached the end of the call's work.
+ *     A call only launches kernels (no memset, no copy), so it may be made while
+ *     `hip_stream` is being captured into a HIP graph; the lengths in
+ *     `seq_lens_host` are then baked into the captured launches.  (The first
+ *     call of a kind in a process also sets a kernel attribute: make one
+ *     uncaptured call of each kind before capturing.)
  *   - `seq_lens_host` is a HOST array of B true lengths (W <= len_b <= N, at
  *     most OBC_MAX_RAGGED_BATCH entries) read before the call returns, or NULL
  *     when every sequence has length N.  The W window queries of sequence b sit
