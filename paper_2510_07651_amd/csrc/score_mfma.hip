@@ -1102,13 +1102,17 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
         const char *qrow = (const char *)q + (((size_t)b * Hq + (size_t)g * G) * W + arow) * kRowBytes;
         const char *orow = (const char *)out_bf16 + (cbase + arow) * kRowBytes;
         const size_t lo_plane = (size_t)gridDim.z * m_pad * kRowBytes;
+        // One array after the other: the four loads that share a 128-byte line of a row follow each other closely.
 #pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
+        for (int kk = 0; kk < 8; ++kk)
             R.q[kk] = ok ? *(const bf16x8 *)(qrow + (2 * kk + half) * 16) : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-            if (kNeedVO) {
+        if (kNeedVO) {
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk)
                 R.ohi[kk] = ok ? *(const bf16x8 *)(orow + (2 * kk + half) * 16) : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk)
                 R.olo[kk] = ok ? *(const bf16x8 *)(orow + lo_plane + (2 * kk + half) * 16) : bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-            }
         }
     }
     // Constants of the 16 rows this lane meets in the accumulators: row rb*32 + 8 (r/4) + 4 half + r%4.
