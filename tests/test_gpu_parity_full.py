@@ -61,6 +61,29 @@ def test_c3_llama_b4_32k_joint():
     print("c3 worst sampled error %.2e" % worst)
 
 
+@pytest.mark.parametrize("sink_gain", [3.0, 1.0])
+def test_c3_shape_with_an_attention_sink(sink_gain):
+    """The metric's shape with queries that share a direction one sink key is aligned with: with gain 3 the sink
+    holds all but 1e-6 or less of every window row's attention, with gain 1 between 1 % and 80 % of it (a quarter at the median) (Appendix C keeps such sinks
+    in the cache; every window row then has a key that is held out of the first sweep's sums)."""
+    import dataclasses
+    wl = dataclasses.replace(synth.config("c3"), shared_query=1.0, sink_gain=sink_gain, sinks=1, seed=3100)
+    x = synth.make_inputs(wl)
+    dev = to_device(x)
+    s = obc.obc_score(dev["q"], dev["k"], dev["v"], "all")
+    torch.cuda.synchronize()
+    heads = [(1, 3), (3, 0)]
+    refs = oracle_scores(x, heads)
+    for vi, name in enumerate(synth.VARIANTS):
+        g_np = s[vi].cpu().numpy()
+        assert np.isfinite(g_np).all() and (g_np >= 0).all()
+        for (b, g), ref3 in zip(heads, refs):
+            err, where = score_error(g_np[b:b + 1, g:g + 1], ref3[vi], wl.budget, None, TOL[wl.dtype])
+            assert err <= TOL[wl.dtype], "sink gain %g %s head (%d,%d): err %.3g at %s" % (sink_gain, name, b, g, err, where)
+            print("c3 with a sink, gain %g, %s head (%d,%d): error %.2e" % (sink_gain, name, b, g, err))
+    _pipeline_checks(wl, x, dev, s[2].contiguous())
+
+
 def test_c4_qwen_128k_all_variants():
     wl = synth.config("c4")
     x = synth.make_inputs(wl)
