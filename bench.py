@@ -195,6 +195,19 @@ def main():
 
     stream(0)
     ms_stream = timed(stream, it, torch)
+    # The same call on inputs where ONE key (an attention sink) holds nearly all of every window row's attention:
+    # its cost must not depend on that (side measurement; the metric above is on the workload's own inputs).
+    import dataclasses
+    sink_wl = dataclasses.replace(wl, shared_query=1.0, sink_gain=3.0, sinks=1)
+    sx = synth.make_inputs(sink_wl, layer=0)
+    sset = {k: (v.to(dev) if torch.is_tensor(v) else v) for k, v in sx.items()}
+
+    def score_sink(i):
+        obc.obc_score(sset["q"], sset["k"], sset["v"], var, seq_lens=lens, scores=scores, workspace=ws)
+
+    score_sink(0)
+    ms_sink = timed(score_sink, it, torch)
+    del sset, sx
     esize = 2 if wl.dtype == "bf16" else 4
     head_tokens = tokens * Hkv
     algo_bytes = head_tokens * 2 * d * esize + B * Hq * W * d * esize + nvar * B * Hkv * N * 4
@@ -255,6 +268,7 @@ def main():
                     "max": round(per_step[-1], 4)},
         "head_tokens_per_s": round(head_tokens / (ms_per_step * 1e-3), 1),
         "score_only_tokens_per_s": round(tokens / (ms["obc_score"] * 1e-3), 1),
+        "obc_score_ms_one_sink_dominates_every_row": round(ms_sink, 4),
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(out))
