@@ -24,9 +24,8 @@
  *     Outputs are valid once that stream has reached the end of the call's work.
  *     A call only launches kernels (no memset, no copy), so it may be made while
  *     `hip_stream` is being captured into a HIP graph; the lengths in
- *     `seq_lens_host` are then baked into the captured launches.  (The first
- *     call of a kind in a process also sets a kernel attribute: make one
- *     uncaptured call of each kind before capturing.)
+ *     `seq_lens_host` are then baked into the captured launches.  No call
+ *     configures anything on first use, so a capture needs no warm-up call.
  *   - `seq_lens_host` is a HOST array of B true lengths (W <= len_b <= N, at
  *     most OBC_MAX_RAGGED_BATCH entries) read before the call returns, or NULL
  *     when every sequence has length N.  The W window queries of sequence b sit
@@ -41,9 +40,9 @@
  *   - obc_score picks its kernels from the shapes: bf16 with head_dim 128 runs on the matrix
  *     cores; a one-row window (W = 1, the decoding case) over a bf16 cache of up to ~1e5
  *     head-tokens runs on kernels shaped for memory round trips; everything else (fp32,
- *     bf16 with head_dim 64 and W > 1) on general vector-ALU kernels.  The environment
- *     variable OBC_SCORE_PATH = plain | mfma | decode pins a path where it applies (for
- *     comparisons and tests); results agree within the tolerance of the dtype on all of them.
+ *     bf16 with head_dim 64 and W > 1) on general vector-ALU kernels.  The routing depends
+ *     on the arguments only (and on obc_set_score_path, a test hook declared at the end of
+ *     this file); the process environment is never read.
  */
 #ifndef OBCACHE_H_
 #define OBCACHE_H_
@@ -121,25 +120,6 @@ int obc_score_accumulate(const void *q, const void *k, const void *v,
                          int N, int W, int Hq, int Hkv, int d, int variant, float *scores,
                          int B, int dtype, const int32_t *seq_lens_host,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
-
-/*
- * Measurement hook: obc_score restricted to some of its stages, so that each kernel
- * of the two-sweep scoring path can be timed on its own with events around the call.
- * Same arguments and checks as obc_score; `stage_mask` is a bit set of
- *   OBC_STAGE_SWEEP1   window attention statistics and outputs (Section 3), per sequence split
- *   OBC_STAGE_COMBINE  merge of the splits into per-row constants
- *   OBC_STAGE_SWEEP2   the scores of Eq. 4-6 from those constants
- * A later stage reads what the earlier ones left in `workspace`, so the first call on a
- * workspace must include all earlier stages.  obc_score == all three.
- */
-#define OBC_STAGE_SWEEP1 1
-#define OBC_STAGE_COMBINE 2
-#define OBC_STAGE_SWEEP2 4
-#define OBC_STAGE_ALL 7
-int obc_score_stages(const void *q, const void *k, const void *v,
-                     int N, int W, int Hq, int Hkv, int d, int variant, float *scores,
-                     int B, int dtype, const int32_t *seq_lens_host,
-                     void *workspace, size_t workspace_bytes, void *hip_stream, int stage_mask);
 
 /*
  * Optional workspace of the three selection calls below.  Heads longer than 32768 tokens
@@ -265,6 +245,31 @@ int obc_compact_inplace(void *k, void *v, float *scores, const int32_t *keep_idx
 int obc_compact_scores(const float *scores, const int32_t *keep_idx, float *scores_out,
                        int B, int Hkv, int N, int budget, int N_out, void *hip_stream);
 
+/* ------------------------------------------------------------------------------------
+ * Measurement and test hooks.  None of these is part of the method; a caller of the
+ * library needs none of them.  They exist so that the benchmark can time single kernels
+ * and the tests can compare the scoring paths with each other.
+ * ------------------------------------------------------------------------------------ */
+
+/*
+ * Measurement hook: obc_score restricted to some of its stages, so that each kernel
+ * of the two-sweep scoring path can be timed on its own with events around the call.
+ * Same arguments and checks as obc_score; `stage_mask` is a bit set of
+ *   OBC_STAGE_SWEEP1   window attention statistics and outputs (Section 3), per sequence split
+ *   OBC_STAGE_COMBINE  merge of the splits into per-row constants
+ *   OBC_STAGE_SWEEP2   the scores of Eq. 4-6 from those constants
+ * A later stage reads what the earlier ones left in `workspace`, so the first call on a
+ * workspace must include all earlier stages.  obc_score == all three.
+ */
+#define OBC_STAGE_SWEEP1 1
+#define OBC_STAGE_COMBINE 2
+#define OBC_STAGE_SWEEP2 4
+#define OBC_STAGE_ALL 7
+int obc_score_stages(const void *q, const void *k, const void *v,
+                     int N, int W, int Hq, int Hkv, int d, int variant, float *scores,
+                     int B, int dtype, const int32_t *seq_lens_host,
+                     void *workspace, size_t workspace_bytes, void *hip_stream, int stage_mask);
+
 /*
  * Measurement hook (not part of the method): reads `bytes` bytes (a multiple of 16, 16-byte
  * aligned, device) once with 128-bit loads and writes one folded word per thread to
@@ -274,6 +279,26 @@ int obc_compact_scores(const float *scores, const int32_t *keep_idx, float *scor
  */
 #define OBC_PROBE_BLOCKS 2048
 int obc_probe_read_bandwidth(const void *buf, size_t bytes, uint32_t *sink, void *hip_stream);
+
+/*
+ * Test hook: pins the kernels obc_score* uses, process-wide, for every later size query and
+ * scoring call (both read the same setting, so a workspace sized by obc_score_workspace_bytes
+ * always fits the call that follows unless the setting is changed in between).
+ *   OBC_PATH_AUTO    routing by shape (the default)
+ *   OBC_PATH_PLAIN   the general vector-ALU kernels for every shape
+ *   OBC_PATH_MFMA    one-row windows stay on the matrix-core kernels
+ *   OBC_PATH_DECODE  one-row windows go to the decode kernels whatever the cache size
+ * Returns OBC_EINVAL for any other value.  Results of all paths agree within the dtype's tolerance.
+ */
+typedef enum { OBC_PATH_AUTO = 0, OBC_PATH_PLAIN = 1, OBC_PATH_MFMA = 2, OBC_PATH_DECODE = 3 } obc_path_t;
+int obc_set_score_path(int path);
+
+/*
+ * Tuning hook: forces the number of sequence splits of the first sweep and the token range of
+ * one workgroup of the second sweep (a multiple of 64 in [64, 65536]) on the matrix-core path,
+ * process-wide; 0 restores the automatic choice.  Values a shape cannot take are ignored for it.
+ */
+int obc_set_score_tuning(int splits, int range_len);
 
 /* Static, human-readable name of a status code. */
 const char *obc_status_string(int status);

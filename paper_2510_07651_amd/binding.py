@@ -79,6 +79,10 @@ def load_library():
     lib.obc_compact_scores.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p]
     lib.obc_probe_read_bandwidth.restype = c_int
     lib.obc_probe_read_bandwidth.argtypes = [c_void_p, c_size_t, c_void_p, c_void_p]
+    lib.obc_set_score_path.restype = c_int
+    lib.obc_set_score_path.argtypes = [c_int]
+    lib.obc_set_score_tuning.restype = c_int
+    lib.obc_set_score_tuning.argtypes = [c_int, c_int]
     _lib = lib
     return lib
 
@@ -126,6 +130,21 @@ def obc_score_workspace_bytes(B, N, W, Hq, Hkv, d, dtype, variant) -> int:
 
 
 OBC_STAGE_SWEEP1, OBC_STAGE_COMBINE, OBC_STAGE_SWEEP2, OBC_STAGE_ALL = 1, 2, 4, 7
+PATH_CODES = {"auto": 0, "plain": 1, "mfma": 2, "decode": 3}
+
+
+def obc_set_score_path(path="auto") -> None:
+    """Test hook: pins the scoring kernels process-wide ("auto" | "plain" | "mfma" | "decode")."""
+    rc = load_library().obc_set_score_path(PATH_CODES[path] if isinstance(path, str) else int(path))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_set_score_path")
+
+
+def obc_set_score_tuning(splits: int = 0, range_len: int = 0) -> None:
+    """Tuning hook: sweep-1 split count and sweep-2 token range of the matrix-core path (0 = automatic)."""
+    rc = load_library().obc_set_score_tuning(int(splits), int(range_len))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_set_score_tuning")
 
 
 def obc_score(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, variant="joint", seq_lens=None,
@@ -177,18 +196,20 @@ def obc_select_workspace_bytes(B: int, Hkv: int, N: int) -> int:
 
 
 def _select_ws(scores: torch.Tensor, workspace):
-    """(pointer, bytes) of the optional selection scratch; allocates it when the shape profits and none was given.
+    """(pointer, bytes, tensor) of the optional selection scratch; allocates it when the shape profits and none was
+    given.  The caller keeps the tensor alive until its C call has enqueued the kernels: torch's allocator hands a
+    freed block to the next allocation on the same stream, which is only safe after the launches that use it.
     workspace=False asks for the one-block-per-head path."""
     if workspace is False:
-        return None, 0
+        return None, 0, None
     B, Hkv, N = scores.shape
     if workspace is None:
         need = obc_select_workspace_bytes(B, Hkv, N)
         if need == 0:
-            return None, 0
-        workspace = torch.empty(need, dtype=torch.uint8, device=scores.device)   # freed stream-ordered by torch
+            return None, 0, None
+        workspace = torch.empty(need, dtype=torch.uint8, device=scores.device)
     _require_cuda(workspace)
-    return workspace.data_ptr(), workspace.numel()
+    return workspace.data_ptr(), workspace.numel(), workspace
 
 
 def obc_select(scores: torch.Tensor, budget: int, seq_lens=None,
@@ -202,9 +223,10 @@ def obc_select(scores: torch.Tensor, budget: int, seq_lens=None,
         keep_idx = torch.empty((B, Hkv, max(int(budget), 0)), dtype=torch.int32, device=scores.device)
     elif keep_idx.dtype != torch.int32 or tuple(keep_idx.shape) != (B, Hkv, int(budget)) or not keep_idx.is_contiguous():
         raise ValueError("keep_idx must be a contiguous [B,Hkv,%d] int32 tensor" % int(budget))
-    ws_ptr, ws_bytes = _select_ws(scores, workspace)
+    ws_ptr, ws_bytes, ws_hold = _select_ws(scores, workspace)
     rc = load_library().obc_select(scores.data_ptr(), int(budget), keep_idx.data_ptr(), B, Hkv, N,
                                    _lens_arg(seq_lens, B), ws_ptr, ws_bytes, _stream_ptr(scores))
+    del ws_hold          # (released only now, after the kernels that use it were enqueued)
     if rc != OBC_OK:
         raise ObcError(rc, "obc_select")
     return keep_idx
@@ -223,10 +245,11 @@ def obc_select_protected(scores: torch.Tensor, num_hh: int, num_sinks: int = 0, 
         keep_idx = torch.empty((B, Hkv, max(total, 0)), dtype=torch.int32, device=scores.device)
     elif keep_idx.dtype != torch.int32 or tuple(keep_idx.shape) != (B, Hkv, total) or not keep_idx.is_contiguous():
         raise ValueError("keep_idx must be a contiguous [B,Hkv,%d] int32 tensor" % total)
-    ws_ptr, ws_bytes = _select_ws(scores, workspace)
+    ws_ptr, ws_bytes, ws_hold = _select_ws(scores, workspace)
     rc = load_library().obc_select_protected(scores.data_ptr(), int(num_hh), int(num_sinks), int(num_recent),
                                              int(num_coming), keep_idx.data_ptr(), B, Hkv, N,
                                              _lens_arg(seq_lens, B), ws_ptr, ws_bytes, _stream_ptr(scores))
+    del ws_hold
     if rc != OBC_OK:
         raise ObcError(rc, "obc_select_protected")
     return keep_idx
@@ -245,10 +268,11 @@ def obc_select_pooled(scores: torch.Tensor, num_hh: int, pool: int = 5, num_sink
         keep_idx = torch.empty((B, Hkv, max(total, 0)), dtype=torch.int32, device=scores.device)
     elif keep_idx.dtype != torch.int32 or tuple(keep_idx.shape) != (B, Hkv, total) or not keep_idx.is_contiguous():
         raise ValueError("keep_idx must be a contiguous [B,Hkv,%d] int32 tensor" % total)
-    ws_ptr, ws_bytes = _select_ws(scores, workspace)
+    ws_ptr, ws_bytes, ws_hold = _select_ws(scores, workspace)
     rc = load_library().obc_select_pooled(scores.data_ptr(), int(num_hh), int(num_sinks), int(num_recent),
                                           int(num_coming), int(pool), keep_idx.data_ptr(), B, Hkv, N,
                                           _lens_arg(seq_lens, B), ws_ptr, ws_bytes, _stream_ptr(scores))
+    del ws_hold
     if rc != OBC_OK:
         raise ObcError(rc, "obc_select_pooled")
     return keep_idx

@@ -61,6 +61,10 @@ struct ScoreWorkspace {
 
 constexpr int kDecodeMaxGroup = 8;   // query heads per KV head the decode path is built for
 
+// Sweep-1 split count and sweep-2 token range forced through obc_set_score_tuning (0: automatic).
+int tuned_splits();
+int tuned_range();
+
 int plan_score_workspace(int B, int N, int W, int Hq, int Hkv, int d, int dtype, int variant, ScoreWorkspace *ws);
 // Adds the matrix-core path's buffers to the plan, advancing *off (bytes).
 void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWorkspace *ws, size_t *off);

@@ -1,11 +1,18 @@
 // Host side of the C ABI declared in include/obcache.h: argument validation, workspace
 // carve-up and kernel dispatch.  Nothing here allocates or synchronises.
-#include <cstdlib>
+#include <atomic>
 #include <cstring>
 
 #include "internal.h"
 
 namespace obc {
+
+// Process-wide routing and tuning set through obc_set_score_path / obc_set_score_tuning.  The size query and
+// the scoring call read the same state, so a plan never depends on anything but its arguments and these.
+static std::atomic<int> g_score_path{OBC_PATH_AUTO};
+static std::atomic<int> g_tuned_splits{0}, g_tuned_range{0};
+int tuned_splits() { return g_tuned_splits.load(std::memory_order_relaxed); }
+int tuned_range() { return g_tuned_range.load(std::memory_order_relaxed); }
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -21,13 +28,10 @@ static int check_score_shape(int B, int N, int W, int Hq, int Hkv, int d, int dt
     return OBC_OK;
 }
 
-// OBC_SCORE_PATH pins the scoring path for comparisons: "plain" routes everything through the
-// general vector-ALU kernels, "mfma" keeps one-row windows on the matrix-core path, "decode"
+// obc_set_score_path pins the scoring path for comparisons: OBC_PATH_PLAIN routes everything through the
+// general vector-ALU kernels, OBC_PATH_MFMA keeps one-row windows on the matrix-core path, OBC_PATH_DECODE
 // sends them to the decode kernels whatever the cache size.
-static bool score_path_is(const char *name) {
-    const char *e = std::getenv("OBC_SCORE_PATH");
-    return e && std::strcmp(e, name) == 0;
-}
+static bool score_path_is(int path) { return g_score_path.load(std::memory_order_relaxed) == path; }
 
 int plan_score_workspace(int B, int N, int W, int Hq, int Hkv, int d, int dtype, int variant, ScoreWorkspace *ws) {
     const int rc = check_score_shape(B, N, W, Hq, Hkv, d, dtype, variant);
@@ -35,21 +39,22 @@ int plan_score_workspace(int B, int N, int W, int Hq, int Hkv, int d, int dtype,
     std::memset(ws, 0, sizeof(*ws));
     const int G = Hq / Hkv;
     const size_t rows = (size_t)B * Hq * W;
-    const bool pinned = score_path_is("plain") || score_path_is("mfma");
-    ws->use_decode = (decode_path_covers(B, N, W, Hq, Hkv, d, dtype, variant, score_path_is("decode")) && !pinned) ? 1 : 0;
-    ws->use_mfma = (!ws->use_decode && dtype == OBC_BF16 && d == 128 && !score_path_is("plain")) ? 1 : 0;
+    const bool pinned = score_path_is(OBC_PATH_PLAIN) || score_path_is(OBC_PATH_MFMA);
+    ws->use_decode = (decode_path_covers(B, N, W, Hq, Hkv, d, dtype, variant, score_path_is(OBC_PATH_DECODE)) && !pinned) ? 1 : 0;
+    ws->use_mfma = (!ws->use_decode && dtype == OBC_BF16 && d == 128 && !score_path_is(OBC_PATH_PLAIN)) ? 1 : 0;
     ws->m_pad = (G * W + 31) / 32 * 32;
     size_t off = 0;
-    ws->row_max = off;  off = align_up(off + rows * sizeof(float), 256);
-    ws->row_sum = off;  off = align_up(off + rows * sizeof(float), 256);
-    ws->out_f32 = off;  off = align_up(off + rows * d * sizeof(float), 256);
-    ws->out_rest_f32 = off;  off = align_up(off + rows * d * sizeof(float), 256);
-    ws->rest_frac = off;  off = align_up(off + rows * sizeof(float), 256);
-    ws->top_token = off;  off = align_up(off + rows * sizeof(int32_t), 256);
     if (ws->use_decode) {
         decode_plan(B, N, Hq, Hkv, d, ws, &off);
     } else if (ws->use_mfma) {
         mfma_plan(B, N, W, Hq, Hkv, d, variant, ws, &off);
+    } else {                                     // the plain path's per-row statistics and outputs
+        ws->row_max = off;  off = align_up(off + rows * sizeof(float), 256);
+        ws->row_sum = off;  off = align_up(off + rows * sizeof(float), 256);
+        ws->out_f32 = off;  off = align_up(off + rows * d * sizeof(float), 256);
+        ws->out_rest_f32 = off;  off = align_up(off + rows * d * sizeof(float), 256);
+        ws->rest_frac = off;  off = align_up(off + rows * sizeof(float), 256);
+        ws->top_token = off;  off = align_up(off + rows * sizeof(int32_t), 256);
     }
     ws->total = align_up(off, 256);
     return OBC_OK;
@@ -74,7 +79,21 @@ using namespace obc;
 
 extern "C" {
 
-int obc_version(void) { return 102; }
+int obc_version(void) { return 103; }
+
+int obc_set_score_path(int path) {
+    if (path < OBC_PATH_AUTO || path > OBC_PATH_DECODE) return OBC_EINVAL;
+    g_score_path.store(path, std::memory_order_relaxed);
+    return OBC_OK;
+}
+
+int obc_set_score_tuning(int splits, int range_len) {
+    if (splits < 0 || range_len < 0 || (range_len != 0 && (range_len < 64 || range_len > 65536 || range_len % 64 != 0)))
+        return OBC_EINVAL;
+    g_tuned_splits.store(splits, std::memory_order_relaxed);
+    g_tuned_range.store(range_len, std::memory_order_relaxed);
+    return OBC_OK;
+}
 
 const char *obc_status_string(int status) {
     switch (status) {

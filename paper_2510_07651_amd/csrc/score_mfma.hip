@@ -45,8 +45,6 @@
 // skips it.  One pass serves every input: nothing is rescanned for rows that turn out dominated.
 //
 // A and Z never touch HBM.  All sums have a fixed order: results are bit-reproducible.
-#include <cstdlib>
-
 #include "internal.h"
 
 namespace obc {
@@ -489,7 +487,7 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
                                                            int Hkv, int ragged, SeqLens lens, int split_len,
                                                            int n_splits, int m_pad, float *__restrict__ part_ml,
                                                            float *__restrict__ part_o) {
-    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    __shared__ __attribute__((aligned(1024))) char smem[kLdsTiles];
     __shared__ int2 ev_list[kNeedO ? kThreads * kEvents : 1];   // per lane: parked former candidates (token, logit bits)
     int2 *events = ev_list + (kNeedO ? threadIdx.x * kEvents : 0);
 
@@ -1040,7 +1038,8 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep2(const uint16_t *__res
     const bool accumulate = accumulate_flag != 0;      // add to what `dst` holds; padded positions stay untouched
     constexpr int kNv = kVariant == OBC_ALL ? 3 : 1;
     constexpr bool kNeedVO = kVariant == OBC_KEY || kVariant == OBC_JOINT || kVariant == OBC_ALL;
-    extern __shared__ __attribute__((aligned(1024))) char smem[];
+    // the K and V tiles, then 256 row constants and the staged partial scores of two tiles
+    __shared__ __attribute__((aligned(1024))) char smem[kLdsTiles + 256 * sizeof(float) + 2 * 4 * kNv * 64 * sizeof(float)];
     float *vis_s = (float *)(smem + kLdsTiles);                // [128] last visible key of each row of the chunk
     float *excl_s = vis_s + 128;                               // [128] key of the row that is scored separately, or -1
     float *part = excl_s + 128;                                // [2 tiles][4 waves][kNv][64] partial scores
@@ -1233,15 +1232,12 @@ __global__ __launch_bounds__(256) void mfma_sum_planes(const float *__restrict__
 template <int kVariant>
 hipError_t launch_sweep2(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStream_t stream) {
     constexpr int nv = kVariant == OBC_ALL ? 3 : 1;
-    const size_t lds = kLdsTiles + 256 * sizeof(float) + (size_t)2 * 4 * nv * 64 * sizeof(float);
-    static const hipError_t lds_ok = hipFuncSetAttribute((const void *)mfma_sweep2<kVariant>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipError_t e = lds_ok;
-    if (e != hipSuccess) return e;
+    hipError_t e;      // (the kernels size their LDS statically: nothing to configure before a launch)
     const size_t plane_elems = (size_t)a.B * a.Hkv * a.N;
     float *dst = ws.n_chunks > 1 ? (float *)(base + ws.planes) : a.scores;
     const size_t chunk_stride = ws.n_chunks > 1 ? plane_elems * nv : 0;
     const dim3 grid((a.N + ws.range_len - 1) / ws.range_len, ws.n_chunks, a.B * a.Hkv);
-    mfma_sweep2<kVariant><<<grid, dim3(kThreads), lds, stream>>>(
+    mfma_sweep2<kVariant><<<grid, dim3(kThreads), 0, stream>>>(
         (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens,
         ws.range_len, ws.m_pad, (const uint16_t *)(base + ws.out_bf16), (const float *)(base + ws.row_const),
         (const float *)(base + ws.special), dst, plane_elems, chunk_stride,
@@ -1264,10 +1260,7 @@ void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWo
     int splits = (512 + BH * ws->n_chunks - 1) / (BH * ws->n_chunks);
     const int max_splits = (N + 511) / 512;
     splits = splits < 1 ? 1 : (splits > max_splits ? max_splits : splits);
-    if (const char *e = std::getenv("OBC_TUNE_SPLITS")) {          // tuning knobs for experiments
-        const int v = std::atoi(e);
-        if (v >= 1 && v <= max_splits) splits = v;
-    }
+    if (const int v = tuned_splits(); v >= 1 && v <= max_splits) splits = v;    // obc_set_score_tuning
     ws->split_len = ((N + splits - 1) / splits + kTileTok - 1) / kTileTok * kTileTok;
     ws->splits = (N + ws->split_len - 1) / ws->split_len;
     // Token range of one sweep-2 block: about two blocks per compute unit over the whole launch.
@@ -1276,10 +1269,7 @@ void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWo
         long long r = ((units + 511) / 512 + 63) / 64 * 64;
         ws->range_len = (int)(r < 128 ? 128 : (r > 8192 ? 8192 : r));
     }
-    if (const char *e = std::getenv("OBC_TUNE_RANGE")) {
-        const int v = std::atoi(e);
-        if (v >= 64 && v <= 65536 && v % 64 == 0) ws->range_len = v;
-    }
+    if (const int v = tuned_range(); v >= 64 && v <= 65536 && v % 64 == 0) ws->range_len = v;
     const size_t rows = (size_t)BH * ws->m_pad;
     ws->out_bf16 = *off;  *off = align_up(*off + 2 * rows * d * 2, 256);   // high pieces, then residual pieces
     ws->row_const = *off; *off = align_up(*off + rows * 4 * sizeof(float), 256);
@@ -1295,18 +1285,13 @@ hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char 
     float *part_ml = (float *)(base + ws.part_ml), *part_o = (float *)(base + ws.part_o);
     hipError_t e = hipSuccess;
     if (a.stage_mask & OBC_STAGE_SWEEP1) {
-        const size_t lds = kLdsTiles;
         const dim3 grid(ws.splits, ws.n_chunks, a.B * a.Hkv);
-        static const hipError_t lds_ok_o = hipFuncSetAttribute((const void *)mfma_sweep1<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsTiles);
-        static const hipError_t lds_ok_n = hipFuncSetAttribute((const void *)mfma_sweep1<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsTiles);
-        e = need_o ? lds_ok_o : lds_ok_n;
-        if (e != hipSuccess) return e;
         if (need_o)
-            mfma_sweep1<true><<<grid, dim3(kThreads), lds, stream>>>(
+            mfma_sweep1<true><<<grid, dim3(kThreads), 0, stream>>>(
                 (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged,
                 a.lens, ws.split_len, ws.splits, ws.m_pad, part_ml, part_o);
         else
-            mfma_sweep1<false><<<grid, dim3(kThreads), lds, stream>>>(
+            mfma_sweep1<false><<<grid, dim3(kThreads), 0, stream>>>(
                 (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged,
                 a.lens, ws.split_len, ws.splits, ws.m_pad, part_ml, part_o);
         e = hipGetLastError();

@@ -74,7 +74,7 @@ __global__ __launch_bounds__(kThreads) void plain_window_attention(
     const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v, int N, int W, int Hq, int Hkv,
     int ragged, SeqLens lens, float *__restrict__ row_max, float *__restrict__ row_sum, float *__restrict__ out,
     float *__restrict__ out_rest, float *__restrict__ rest_frac, int32_t *__restrict__ top_token) {
-    extern __shared__ float smem[];
+    __shared__ float smem[OBC_MAX_WINDOW * D + kTile * (D + 1) + OBC_MAX_WINDOW * (kTile + 1) + 2 * OBC_MAX_WINDOW];
     float *qs = smem;                                // [OBC_MAX_WINDOW][D]
     float *ts = qs + OBC_MAX_WINDOW * D;             // [kTile][D+1]  K tile, then V tile
     float *ps = ts + kTile * (D + 1);                // [OBC_MAX_WINDOW][kTile+1] unnormalised weights of the tile
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(kThreads) void plain_score(
     int ragged, SeqLens lens, int variant, const float *__restrict__ row_max, const float *__restrict__ row_sum,
     const float *__restrict__ out, const float *__restrict__ out_rest, const float *__restrict__ rest_frac,
     const int32_t *__restrict__ top_token, float *__restrict__ scores, size_t variant_stride, int accumulate) {
-    extern __shared__ float smem[];
+    __shared__ float smem[2 * kTile * (D + 1) + 4 * D + 4 * kTile * 3];
     float *ks = smem;                          // [kTile][D+1]
     float *vs = ks + kTile * (D + 1);          // [kTile][D+1]
     float *qs = vs + kTile * (D + 1);          // [4][D] the query row each wave is working on
@@ -291,15 +291,9 @@ hipError_t run(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStre
     float *out = (float *)(base + ws.out_f32), *out_rest = (float *)(base + ws.out_rest_f32);
     float *rest_frac = (float *)(base + ws.rest_frac);
     int32_t *top_token = (int32_t *)(base + ws.top_token);
-    const size_t lds1 = sizeof(float) * (OBC_MAX_WINDOW * D + kTile * (D + 1) + OBC_MAX_WINDOW * (kTile + 1) + 2 * OBC_MAX_WINDOW);
-    const size_t lds2 = sizeof(float) * (2 * kTile * (D + 1) + 4 * D + 4 * kTile * 3);
-    hipError_t e;
-    e = hipFuncSetAttribute((const void *)plain_window_attention<T, D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds1);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void *)plain_score<T, D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
-    if (e != hipSuccess) return e;
+    hipError_t e;      // (both kernels size their LDS statically: nothing to configure before a launch)
     if (a.stage_mask & OBC_STAGE_SWEEP1) {      // the plain path has no separate combine stage
-        plain_window_attention<T, D><<<dim3(a.B * a.Hq), dim3(kThreads), lds1, stream>>>(
+        plain_window_attention<T, D><<<dim3(a.B * a.Hq), dim3(kThreads), 0, stream>>>(
             (const T *)a.q, (const T *)a.k, (const T *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, row_max, row_sum,
             out, out_rest, rest_frac, top_token);
         e = hipGetLastError();
@@ -307,7 +301,7 @@ hipError_t run(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, hipStre
     }
     if (!(a.stage_mask & OBC_STAGE_SWEEP2)) return hipSuccess;
     const dim3 grid((a.N + kTile - 1) / kTile, a.B * a.Hkv);
-    plain_score<T, D><<<grid, dim3(kThreads), lds2, stream>>>(
+    plain_score<T, D><<<grid, dim3(kThreads), 0, stream>>>(
         (const T *)a.q, (const T *)a.k, (const T *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens, a.variant, row_max,
         row_sum, out, out_rest, rest_frac, top_token, a.scores, (size_t)a.B * a.Hkv * a.N, a.accumulate);
     return hipGetLastError();

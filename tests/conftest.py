@@ -16,3 +16,13 @@ def pytest_collection_modifyitems(config, items):
     """GPU tests fail loudly (not skip) when selected on a box without a GPU; they are
     deselected by -m "not gpu" on CPU-only hosts."""
     return
+
+
+@pytest.fixture
+def score_path():
+    """Pins the scoring kernels for the duration of a test (obc_set_score_path) and restores the routing by shape."""
+    from paper_2510_07651_amd import binding as obc
+
+    yield obc.obc_set_score_path
+    obc.obc_set_score_path("auto")
+    obc.obc_set_score_tuning(0, 0)

@@ -138,6 +138,46 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     assert ip(fake, fake, None, fake, 1, 1, 16, 4, 64, 7, None) == obc.OBC_EUNSUPPORTED      # dtype
 
 
+def test_plan_ignores_the_process_environment_and_follows_the_hooks(lib, monkeypatch):
+    """The workspace plan is a function of the arguments and of obc_set_score_path / obc_set_score_tuning alone:
+    changing the environment between the size query and the call cannot make them disagree."""
+    c3 = (4, 32768, 32, 32, 8, 128, obc.OBC_BF16, obc.OBC_JOINT)
+    dec = (1, 1025, 1, 32, 8, 128, obc.OBC_BF16, obc.OBC_JOINT)
+    base = [obc.obc_score_workspace_bytes(*a) for a in (c3, dec)]
+    for name, value in (("OBC_SCORE_PATH", "plain"), ("OBC_TUNE_SPLITS", "3"), ("OBC_TUNE_RANGE", "128")):
+        monkeypatch.setenv(name, value)
+    assert [obc.obc_score_workspace_bytes(*a) for a in (c3, dec)] == base
+    # the call after an environment change still accepts a workspace of exactly the queried size: it gets past the
+    # workspace check (with no GPU here the launch itself then fails)
+    fake = ctypes.c_void_p(1 << 20)
+    import torch
+    if not torch.cuda.is_available():      # (with a GPU present the made-up pointers must never reach a kernel)
+        rc = lib.obc_score(fake, fake, fake, 32768, 32, 32, 8, 128, 2, fake, 4, 1, None, fake, base[0], None)
+        assert rc == obc.OBC_ELAUNCH
+    assert lib.obc_score(fake, fake, fake, 32768, 32, 32, 8, 128, 2, fake, 4, 1, None, fake, base[0] - 256,
+                         None) == obc.OBC_EWORKSPACE
+    # the matrix-core plan holds no buffer of the plain path: forcing the plain path changes the size
+    try:
+        obc.obc_set_score_path("plain")
+        plain = obc.obc_score_workspace_bytes(*c3)
+        assert plain != base[0] and plain >= 2 * 4 * 32 * 32 * 128 * 4
+        obc.obc_set_score_path("mfma")
+        assert obc.obc_score_workspace_bytes(*dec) != base[1]          # one-row window kept on the matrix cores
+        obc.obc_set_score_path("auto")
+        obc.obc_set_score_tuning(4, 256)
+        assert obc.obc_score_workspace_bytes(*c3) < base[0]            # fewer splits, smaller partial records
+        with pytest.raises(obc.ObcError):
+            obc.obc_set_score_tuning(4, 100)                           # not a multiple of 64
+        with pytest.raises(obc.ObcError):
+            obc.obc_set_score_path(9)
+    finally:
+        obc.obc_set_score_path("auto")
+        obc.obc_set_score_tuning(0, 0)
+    assert [obc.obc_score_workspace_bytes(*a) for a in (c3, dec)] == base
+    # c3's workspace: the split partials dominate (16 splits x 4096 rows x 132 floats) and nothing of the plain path is in it
+    assert base[0] < 16 * 4096 * 132 * 4 + (4 << 20)
+
+
 def test_bench_refuses_more_than_one_gpu():
     """One GPU per box in this build: bench.py says so and exits instead of launching collectives."""
     import subprocess

@@ -44,8 +44,8 @@ CASES = {w.name: w for w in [
 
 
 @pytest.mark.parametrize("name", list(CASES))
-def test_decode_scores_select_compact_match_oracle(name, monkeypatch):
-    monkeypatch.setenv("OBC_SCORE_PATH", "decode")      # whatever the size (long caches go to the matrix cores otherwise)
+def test_decode_scores_select_compact_match_oracle(name, score_path):
+    score_path("decode")      # whatever the size (long caches go to the matrix cores otherwise)
     worst = run_case(CASES[name])
     print(name, {k: "%.2e" % v for k, v in worst.items()})
 
@@ -59,8 +59,8 @@ def test_attention_mass_of_the_dominant_case():
 
 
 @pytest.mark.parametrize("name", ["d_llama_1025", "d_qwen_g7", "d_g2_ragged", "d_long_separate_merge", "d_mha_d64"])
-def test_decode_attention_only_and_vatp_match_oracle(name, monkeypatch):
-    monkeypatch.setenv("OBC_SCORE_PATH", "decode")
+def test_decode_attention_only_and_vatp_match_oracle(name, score_path):
+    score_path("decode")
     wl = CASES[name]
     x = synth.make_inputs(wl)
     dev = to_device(x)
@@ -74,8 +74,8 @@ def test_decode_attention_only_and_vatp_match_oracle(name, monkeypatch):
 
 
 @pytest.mark.parametrize("name", ["d_llama_1025", "d_long_separate_merge"])
-def test_decode_accumulate_adds_and_leaves_padding_alone(name, monkeypatch):
-    monkeypatch.setenv("OBC_SCORE_PATH", "decode")
+def test_decode_accumulate_adds_and_leaves_padding_alone(name, score_path):
+    score_path("decode")
     wl = CASES[name]
     x = synth.make_inputs(wl)
     dev = to_device(x)
@@ -92,9 +92,9 @@ def test_decode_accumulate_adds_and_leaves_padding_alone(name, monkeypatch):
         assert torch.equal(again, inc), "decode scoring must be bit-reproducible"
 
 
-def test_matrix_core_path_still_serves_one_row_windows(monkeypatch):
-    """OBC_SCORE_PATH=mfma keeps W = 1 on the matrix-core kernels; both paths must meet the oracle."""
-    monkeypatch.setenv("OBC_SCORE_PATH", "mfma")
+def test_matrix_core_path_still_serves_one_row_windows(score_path):
+    """The matrix-core pin keeps W = 1 on the matrix-core kernels; both paths must meet the oracle."""
+    score_path("mfma")
     run_case(CASES["d_llama_1025"])
     run_case(CASES["d_one_key_takes_all"])
     run_case(CASES["d_one_key_takes_all_harder"])

@@ -139,8 +139,8 @@ CASES = {
 
 @pytest.mark.gpu
 @pytest.mark.parametrize("name", list(CASES))
-def test_dominant_rows_match_oracle(name, monkeypatch):
-    monkeypatch.setenv("OBC_SCORE_PATH", "mfma")
+def test_dominant_rows_match_oracle(name, score_path):
+    score_path("mfma")
     x = CASES[name]()
     lens = x["seq_lens"]
     ref = oracle.score(x["q"], x["k"], x["v"], seq_lens=lens)

@@ -33,10 +33,24 @@ def test_deterministic_bits():
     assert torch.equal(a, b)
 
 
-def test_plain_path_env_switch(monkeypatch):
+def test_plain_path_switch(score_path):
     """The vector-ALU path serves bf16 head_dim-128 inputs too when asked to; it must agree with the oracle."""
-    monkeypatch.setenv("OBC_SCORE_PATH", "plain")
+    score_path("plain")
     _run_case(CASES["s_bf16_ragged"])
+
+
+def test_environment_change_between_size_query_and_call(monkeypatch):
+    """A workspace of exactly the queried size is accepted whatever the process environment does in between."""
+    wl = CASES["s_bf16_llama"]
+    x = synth.make_inputs(wl)
+    dev = to_device(x)
+    need = obc.obc_score_workspace_bytes(wl.B, wl.N, wl.W, wl.Hq, wl.Hkv, wl.d, obc.OBC_BF16, obc.OBC_JOINT)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    first = obc.obc_score(dev["q"], dev["k"], dev["v"], "joint", seq_lens=x["seq_lens"], workspace=ws).clone()
+    for name, value in (("OBC_SCORE_PATH", "plain"), ("OBC_TUNE_SPLITS", "1"), ("OBC_TUNE_RANGE", "8192")):
+        monkeypatch.setenv(name, value)
+    again = obc.obc_score(dev["q"], dev["k"], dev["v"], "joint", seq_lens=x["seq_lens"], workspace=ws)
+    assert torch.equal(first, again)
 
 
 def test_select_crafted_ties_and_specials():
