@@ -122,6 +122,30 @@ int obc_score_accumulate(const void *q, const void *k, const void *v,
                          void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * For callers that cannot allocate or size a workspace: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid device allocation.  obc_score (accumulate = 0) or
+ * obc_score_accumulate (accumulate = 1) with the library's own scratch in place of the
+ * `workspace` argument: a device array of OBC_STATIC_SCRATCH_BYTES that is part of the loaded
+ * library (one copy per GPU, held until the process ends).  Same inputs, outputs, checks and
+ * results as those calls; nothing is allocated, freed, copied or synchronised.
+ *   - Shapes whose obc_score_workspace_bytes exceeds OBC_STATIC_SCRATCH_BYTES are rejected with
+ *     OBC_EWORKSPACE before anything is launched (the metric's workload, 4 x 32768 tokens of a
+ *     32/8-head layer, needs ~35 MiB and fits; decode steps need well under 1 MiB).
+ *   - Every call on one GPU shares that GPU's array.  The scratch carries no state between
+ *     calls (each call overwrites what it reads), but two calls in flight on the same GPU at
+ *     the same time (different streams, or graphs replayed concurrently) race on it: keep calls
+ *     of this entry point on one GPU ordered.
+ *   - obc_init() looks the array's device address up for the current device (once per device);
+ *     without it the first obc_score_static call on a device does so itself.  Call obc_init()
+ *     before capturing a graph that contains this call.  OBC_ELAUNCH if the lookup fails.
+ */
+#define OBC_STATIC_SCRATCH_BYTES (48u << 20)
+int obc_init(void);
+int obc_score_static(const void *q, const void *k, const void *v,
+                     int N, int W, int Hq, int Hkv, int d, int variant, float *scores,
+                     int B, int dtype, const int32_t *seq_lens_host, int accumulate, void *hip_stream);
+
+/*
  * Optional workspace of the three selection calls below.  Heads longer than 32768 tokens
  * do not fit one block's registers; given *bytes_out bytes of 256-byte aligned device
  * scratch their selection is cut into slices of 8192 tokens that run on separate blocks.

@@ -79,6 +79,10 @@ def load_library():
     lib.obc_compact_scores.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_void_p]
     lib.obc_probe_read_bandwidth.restype = c_int
     lib.obc_probe_read_bandwidth.argtypes = [c_void_p, c_size_t, c_void_p, c_void_p]
+    lib.obc_init.restype = c_int
+    lib.obc_score_static.restype = c_int
+    lib.obc_score_static.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p,
+                                     c_int, c_int, i32p, c_int, c_void_p]
     lib.obc_set_score_path.restype = c_int
     lib.obc_set_score_path.argtypes = [c_int]
     lib.obc_set_score_tuning.restype = c_int
@@ -184,6 +188,34 @@ def obc_score(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, variant="joint"
         rc = load_library().obc_score_stages(*args, int(stage_mask))
     if rc != OBC_OK:
         raise ObcError(rc, "obc_score")
+    return scores
+
+
+OBC_STATIC_SCRATCH_BYTES = 48 << 20
+
+
+def obc_init() -> None:
+    rc = load_library().obc_init()
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_init")
+
+
+def obc_score_static(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, variant, scores: torch.Tensor, seq_lens=None,
+                     accumulate: bool = False) -> torch.Tensor:
+    """obc_score / obc_score_accumulate on the library's static scratch: the caller passes inputs and the output
+    tensor, and nothing is allocated (not by torch either)."""
+    _require_cuda(q, k, v, scores)
+    B, Hq, W, d = q.shape
+    _, Hkv, N, _ = k.shape
+    var = VARIANT_CODES[variant] if isinstance(variant, str) else int(variant)
+    shape = (3, B, Hkv, N) if var == OBC_ALL else (B, Hkv, N)
+    if tuple(scores.shape) != shape or scores.dtype != torch.float32 or v.shape != k.shape:
+        raise ValueError("scores must be a contiguous float32 tensor of shape %s" % (shape,))
+    rc = load_library().obc_score_static(q.data_ptr(), k.data_ptr(), v.data_ptr(), N, W, Hq, Hkv, d, var,
+                                         scores.data_ptr(), B, _dtype_code(q), _lens_arg(seq_lens, B),
+                                         1 if accumulate else 0, _stream_ptr(q))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_score_static")
     return scores
 
 

@@ -2,8 +2,13 @@
 // carve-up and kernel dispatch.  Nothing here allocates or synchronises.
 #include <atomic>
 #include <cstring>
+#include <mutex>
 
 #include "internal.h"
+
+// Scratch of obc_score_static: one copy per GPU the library is loaded on, held until the process ends.
+// Host code never uses this name as an address; it asks the runtime for the device address once per device.
+static __device__ __align__(256) unsigned char scratch[OBC_STATIC_SCRATCH_BYTES];
 
 namespace obc {
 
@@ -13,6 +18,27 @@ static std::atomic<int> g_score_path{OBC_PATH_AUTO};
 static std::atomic<int> g_tuned_splits{0}, g_tuned_range{0};
 int tuned_splits() { return g_tuned_splits.load(std::memory_order_relaxed); }
 int tuned_range() { return g_tuned_range.load(std::memory_order_relaxed); }
+
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kMaxDevices];
+static hipError_t static_scratch(void **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> hold(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p || ((uintptr_t)p & 255) != 0) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
@@ -81,6 +107,11 @@ extern "C" {
 
 int obc_version(void) { return 103; }
 
+int obc_init(void) {
+    void *p = nullptr;
+    return static_scratch(&p) == hipSuccess ? OBC_OK : OBC_ELAUNCH;
+}
+
 int obc_set_score_path(int path) {
     if (path < OBC_PATH_AUTO || path > OBC_PATH_DECODE) return OBC_EINVAL;
     g_score_path.store(path, std::memory_order_relaxed);
@@ -100,7 +131,7 @@ const char *obc_status_string(int status) {
         case OBC_OK: return "OBC_OK";
         case OBC_EINVAL: return "OBC_EINVAL: invalid argument";
         case OBC_EUNSUPPORTED: return "OBC_EUNSUPPORTED: shape or dtype not supported by the gfx950 kernels";
-        case OBC_EWORKSPACE: return "OBC_EWORKSPACE: workspace missing, misaligned or too small";
+        case OBC_EWORKSPACE: return "OBC_EWORKSPACE: workspace missing, misaligned or too small (obc_score_static: the shape needs more than OBC_STATIC_SCRATCH_BYTES)";
         case OBC_ELAUNCH: return "OBC_ELAUNCH: HIP launch error";
         default: return "unknown obcache status";
     }
@@ -141,9 +172,20 @@ int obc_score_accumulate(const void *q, const void *k, const void *v, int N, int
                       hip_stream, OBC_STAGE_ALL, 1);
 }
 
+int obc_score_static(const void *q, const void *k, const void *v, int N, int W, int Hq, int Hkv, int d, int variant,
+                     float *scores, int B, int dtype, const int32_t *seq_lens_host, int accumulate, void *hip_stream) {
+    if (accumulate != 0 && accumulate != 1) return OBC_EINVAL;
+    // (workspace == NULL with the largest size: score_impl takes the library's own scratch and checks the plan against it)
+    return score_impl(q, k, v, N, W, Hq, Hkv, d, variant, scores, B, dtype, seq_lens_host, nullptr,
+                      OBC_STATIC_SCRATCH_BYTES, hip_stream, OBC_STAGE_ALL, accumulate | 2);
+}
+
+// `accumulate` bit 0: add to the scores; bit 1: use the library's static scratch (workspace must be NULL).
 static int score_impl(const void *q, const void *k, const void *v, int N, int W, int Hq, int Hkv, int d, int variant,
                       float *scores, int B, int dtype, const int32_t *seq_lens_host, void *workspace,
                       size_t workspace_bytes, void *hip_stream, int stage_mask, int accumulate) {
+    const bool own_scratch = (accumulate & 2) != 0;
+    accumulate &= 1;
     if (!q || !k || !v || !scores) return OBC_EINVAL;
     if ((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v) & 15) != 0 || ((uintptr_t)scores & 3) != 0) return OBC_EINVAL;
     if (stage_mask < 1 || stage_mask > OBC_STAGE_ALL) return OBC_EINVAL;
@@ -154,6 +196,10 @@ static int score_impl(const void *q, const void *k, const void *v, int N, int W,
     std::memset(&a, 0, sizeof(a));
     rc = fill_lens(seq_lens_host, B, N, W, &a.ragged, &a.lens);
     if (rc != OBC_OK) return rc;
+    if (own_scratch) {
+        if (ws.total > workspace_bytes) return OBC_EWORKSPACE;           // the shape does not fit the static scratch
+        if (static_scratch(&workspace) != hipSuccess) return OBC_ELAUNCH;
+    }
     if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < ws.total) return OBC_EWORKSPACE;
     a.q = q; a.k = k; a.v = v; a.scores = scores;
     a.B = B; a.N = N; a.W = W; a.Hq = Hq; a.Hkv = Hkv; a.d = d; a.G = Hq / Hkv;
