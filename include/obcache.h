@@ -324,6 +324,15 @@ int obc_set_score_path(int path);
  */
 int obc_set_score_tuning(int splits, int range_len);
 
+/*
+ * Test hook: form of the matrix-core path's second sweep for the variants with a cross term (key, joint, all),
+ * process-wide.  0: chosen by shape; 1: 32 window rows per wave, two workgroups per compute unit; 2: 64 rows per
+ * wave with the stationary operands in the accumulator registers, one workgroup per compute unit, wherever the
+ * row count allows (every 128-row chunk at least three quarters full).  Both forms meet the same tolerance; their
+ * sums run in different orders, so their low bits differ.
+ */
+int obc_set_sweep2_form(int form);
+
 /* Static, human-readable name of a status code. */
 const char *obc_status_string(int status);
 

@@ -87,6 +87,8 @@ def load_library():
     lib.obc_set_score_path.argtypes = [c_int]
     lib.obc_set_score_tuning.restype = c_int
     lib.obc_set_score_tuning.argtypes = [c_int, c_int]
+    lib.obc_set_sweep2_form.restype = c_int
+    lib.obc_set_sweep2_form.argtypes = [c_int]
     _lib = lib
     return lib
 
@@ -142,6 +144,13 @@ def obc_set_score_path(path="auto") -> None:
     rc = load_library().obc_set_score_path(PATH_CODES[path] if isinstance(path, str) else int(path))
     if rc != OBC_OK:
         raise ObcError(rc, "obc_set_score_path")
+
+
+def obc_set_sweep2_form(form: int = 0) -> None:
+    """Test hook: 0 = second sweep chosen by shape, 1 = 32 rows per wave, 2 = 64 rows per wave where possible."""
+    rc = load_library().obc_set_sweep2_form(int(form))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_set_sweep2_form")
 
 
 def obc_set_score_tuning(splits: int = 0, range_len: int = 0) -> None:

@@ -16,7 +16,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(CSRC, "_build")
 LIB = os.path.join(HERE, "libobcache.so")
-SOURCES = ["obc_api.hip", "score_plain.hip", "score_mfma.hip", "score_decode.hip", "select.hip", "compact.hip"]
+SOURCES = ["obc_api.hip", "score_plain.hip", "score_mfma.hip", "score_mfma_wide.hip", "score_decode.hip", "select.hip", "compact.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]

@@ -48,6 +48,7 @@ struct ScoreWorkspace {
     int split_len;     // tokens per split (multiple of 64)
     int range_len;     // tokens per workgroup in the second sweep (multiple of 64)
     int use_mfma;      // 1: matrix-core path, 0: plain path
+    int use_wide;      // 1: the second sweep runs in its register-blocked form (score_mfma_wide.hip)
     // Decode path (one window row per query head): see score_decode.hip.
     size_t dec_z;      // float [B*Hkv*N*dec_rows]  scaled logits, token-major
     size_t dec_part;   // float [B*Hkv*dec_splits*dec_rows*(d+4)]  per-range partial records
@@ -64,6 +65,7 @@ constexpr int kDecodeMaxGroup = 8;   // query heads per KV head the decode path 
 // Sweep-1 split count and sweep-2 token range forced through obc_set_score_tuning (0: automatic).
 int tuned_splits();
 int tuned_range();
+int tuned_sweep2_form();     // 0: by shape, 1: 32 rows per wave, 2: 64 rows per wave where the shape allows
 
 int plan_score_workspace(int B, int N, int W, int Hq, int Hkv, int d, int dtype, int variant, ScoreWorkspace *ws);
 // Adds the matrix-core path's buffers to the plan, advancing *off (bytes).
@@ -77,6 +79,11 @@ hipError_t launch_score_decode(const ScoreArgs &a, const ScoreWorkspace &ws, cha
 // Launchers.  Each enqueues on `stream` and returns hipSuccess or the launch error.
 hipError_t launch_score_plain(const ScoreArgs &a, const ScoreWorkspace &ws, char *ws_base, hipStream_t stream);
 hipError_t launch_score_mfma(const ScoreArgs &a, const ScoreWorkspace &ws, char *ws_base, hipStream_t stream);
+// Register-blocked second sweep: whether it serves the variant and row count, and its launcher (same arguments
+// and outputs as the 32-rows-per-wave kernel it stands in for).
+bool sweep2_wide_covers(int variant, int m_pad, int M);
+hipError_t launch_sweep2_wide(const ScoreArgs &a, const ScoreWorkspace &ws, char *base, float *dst, size_t plane_elems,
+                              size_t chunk_stride, hipStream_t stream);
 hipError_t launch_select(const float *scores, int budget, int32_t *keep_idx, int B, int Hkv, int N, int ragged,
                          const SeqLens &lens, int first, int tail, int radius, void *workspace,
                          size_t workspace_bytes, hipStream_t stream, int keys_in = 0);

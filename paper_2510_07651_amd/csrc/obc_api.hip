@@ -15,9 +15,10 @@ namespace obc {
 // Process-wide routing and tuning set through obc_set_score_path / obc_set_score_tuning.  The size query and
 // the scoring call read the same state, so a plan never depends on anything but its arguments and these.
 static std::atomic<int> g_score_path{OBC_PATH_AUTO};
-static std::atomic<int> g_tuned_splits{0}, g_tuned_range{0};
+static std::atomic<int> g_tuned_splits{0}, g_tuned_range{0}, g_tuned_form{0};
 int tuned_splits() { return g_tuned_splits.load(std::memory_order_relaxed); }
 int tuned_range() { return g_tuned_range.load(std::memory_order_relaxed); }
+int tuned_sweep2_form() { return g_tuned_form.load(std::memory_order_relaxed); }
 
 // Device address of `scratch` on the current device, looked up once per device.
 constexpr int kMaxDevices = 64;
@@ -115,6 +116,12 @@ int obc_init(void) {
 int obc_set_score_path(int path) {
     if (path < OBC_PATH_AUTO || path > OBC_PATH_DECODE) return OBC_EINVAL;
     g_score_path.store(path, std::memory_order_relaxed);
+    return OBC_OK;
+}
+
+int obc_set_sweep2_form(int form) {
+    if (form < 0 || form > 2) return OBC_EINVAL;
+    g_tuned_form.store(form, std::memory_order_relaxed);
     return OBC_OK;
 }
 

@@ -46,222 +46,11 @@
 //
 // A and Z never touch HBM.  All sums have a fixed order: results are bit-reproducible.
 #include "internal.h"
+#include "mfma_util.h"
 
 namespace obc {
+using namespace mfma;
 namespace {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef __attribute__((__vector_size__(4 * sizeof(short)))) short i16x4;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-typedef __bf16 bf16_2 __attribute__((ext_vector_type(2)));
-typedef float f32_2 __attribute__((ext_vector_type(2)));
-
-constexpr int kD = 128;                 // head_dim
-constexpr int kRowBytes = kD * 2;       // one bf16 K or V row
-constexpr int kTileTok = 64;            // tokens per LDS tile (two blocks of 32)
-constexpr int kTileBytes = kTileTok * kRowBytes;   // 16 KB
-constexpr int kThreads = 256;           // 4 waves; wave w owns row block 4*chunk + w (32 window rows)
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kInvSqrtD = 0.08838834764831845f;   // 1/sqrt(128)
-// The running softmax sums of sweep 1 are kept relative to a reference that follows the
-// running max lazily: it only moves (and the accumulated O is only rescaled) when the max
-// has grown by more than 8 in log2 units, so weights stay below 2^8 and the 64-register
-// rescale becomes rare instead of happening whenever any of a wave's 32 rows sees a new max.
-constexpr float kLazyRescale = 8.0f / (kLog2e * kInvSqrtD);   // in raw q.k units
-
-// LDS map (bytes) of sweep 2: two K tiles, then two V tiles.  Sweep 1 uses
-// the same 64 KB as a ring of four 8 KB K blocks followed by a ring of four V blocks.
-constexpr int kLdsK0 = 0, kLdsK1 = kTileBytes, kLdsV0 = 2 * kTileBytes, kLdsV1 = 3 * kTileBytes;
-constexpr int kLdsTiles = 4 * kTileBytes;           // 64 KB
-
-enum Swizzle { kXor16 = 0, kRot4 = 1 };
-
-// LDS tiles hold 64 rows of 256 B.  Row R keeps its 16-byte piece c at slot
-//   kXor16: c ^ (R & 15)         -- conflict-free when 16 lanes read the same piece of 16 consecutive rows
-//   kRot4 : (c + 4 (R & 3)) & 15 -- conflict-free when 32 lanes read 64 contiguous bytes of 4 consecutive rows
-__device__ __forceinline__ int piece_of(int swz, int R, int slot) {
-    return swz == kXor16 ? (slot ^ (R & 15)) : ((slot - 4 * (R & 3)) & 15);
-}
-
-__device__ __forceinline__ uint32_t lds_offset_of(const void *p) {
-    return (uint32_t)(size_t)(const __attribute__((address_space(3))) char *)p;
-}
-
-// One direct-to-LDS transfer: every lane supplies the address of 16 bytes in global
-// memory; the wave's 1 KB lands contiguously at LDS byte `lds_off` (lane l at +16 l).
-// Issued from inline assembly so that the compiler's wait-count bookkeeping does not tie
-// later LDS reads of OTHER tiles to these transfers; the kernels wait for them
-// explicitly (wait_async_loads + barrier) before the tile is read.
-__device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_off) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_off), "v"(gptr) : "memory");
-}
-// Same transfer with the address split into a wave-uniform 64-bit base (scalar registers)
-// and a per-lane 32-bit byte offset: no vector-ALU address arithmetic per transfer.
-__device__ __forceinline__ void dma16_based(const void *sbase, uint32_t voff, uint32_t lds_off) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_off), "v"(voff), "s"(sbase) : "memory");
-}
-__device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
-// Asynchronous copy of one 64-row tile.  Each wave issues four transfers; lane l of
-// transfer n lands at row 4 (4 wave + n) + l / 16, slot l % 16, and picks the global piece
-// that belongs in that slot.  Rows past `last_row` re-read `last_row` (memory beyond the
-// true length is never touched).
-// Per-lane byte offsets of the four transfers inside a tile whose 64 rows all exist.
-template <int SWZ>
-__device__ __forceinline__ void tile_lane_offsets(uint32_t (&doff)[4], int wave, int lane) {
-#pragma unroll
-    for (int n = 0; n < 4; ++n) {
-        const int R = (wave * 4 + n) * 4 + (lane >> 4);
-        doff[n] = (uint32_t)(R * kRowBytes + piece_of(SWZ, R, lane & 15) * 16);
-    }
-}
-
-template <int SWZ>
-__device__ __forceinline__ void tile_load_async(const char *__restrict__ head_base, int t0, int last_row,
-                                                uint32_t lds_tile, int wave, int lane, const uint32_t (&doff)[4]) {
-    if (t0 + kTileTok - 1 <= last_row) {            // uniform: the common case, every row of the tile exists
-        const char *sbase = head_base + (size_t)t0 * kRowBytes;
-#pragma unroll
-        for (int n = 0; n < 4; ++n) dma16_based(sbase, doff[n], lds_tile + (wave * 4 + n) * 1024);
-        return;
-    }
-#pragma unroll
-    for (int n = 0; n < 4; ++n) {
-        const int R = (wave * 4 + n) * 4 + (lane >> 4);
-        const int c = piece_of(SWZ, R, lane & 15);
-        int row = t0 + R;
-        row = row > last_row ? last_row : row;
-        dma16(head_base + (size_t)row * kRowBytes + c * 16, lds_tile + (wave * 4 + n) * 1024);
-    }
-}
-
-// The same for one 32-row block (8 KB): two transfers per wave, wave w brings rows 8w .. 8w+7.
-constexpr int kBlkBytes = 32 * kRowBytes;
-template <int SWZ>
-__device__ __forceinline__ void block_lane_offsets(uint32_t (&doff)[2], int wave, int lane) {
-#pragma unroll
-    for (int n = 0; n < 2; ++n) {
-        const int R = (wave * 2 + n) * 4 + (lane >> 4);
-        doff[n] = (uint32_t)(R * kRowBytes + piece_of(SWZ, R, lane & 15) * 16);
-    }
-}
-template <int SWZ>
-__device__ __forceinline__ void block_load_async(const char *__restrict__ head_base, int t0, int last_row,
-                                                 uint32_t lds_block, int wave, int lane, const uint32_t (&doff)[2]) {
-    if (t0 + 31 <= last_row) {                      // uniform: every row of the block exists
-        const char *sbase = head_base + (size_t)t0 * kRowBytes;
-#pragma unroll
-        for (int n = 0; n < 2; ++n) dma16_based(sbase, doff[n], lds_block + (wave * 2 + n) * 1024);
-        return;
-    }
-#pragma unroll
-    for (int n = 0; n < 2; ++n) {                   // rows past the end re-read the last row
-        const int R = (wave * 2 + n) * 4 + (lane >> 4);
-        const int c = piece_of(SWZ, R, lane & 15);
-        int row = t0 + R;
-        row = row > last_row ? last_row : row;
-        dma16(head_base + (size_t)row * kRowBytes + c * 16, lds_block + (wave * 2 + n) * 1024);
-    }
-}
-// Waits until at most kKeep of this wave's most recent transfers are still in flight
-// (transfers complete in issue order; other memory operations in flight only make the wait stricter).
-template <int kKeep>
-__device__ __forceinline__ void wait_async_loads_keep() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kKeep) : "memory"); }
-
-// Per-lane byte offset, inside a kXor16 tile, of piece 2 kk + half of row (lane % 32) of a
-// 32-row block; add 32 * 256 for the tile's second block.  16-byte matrix-core operand:
-// K as the A operand of K Q^T, K and V as B operands of Q K^T and O V^T.
-__device__ __forceinline__ int row_piece_offset(int lane, int kk) {
-    const int R = lane & 31, c = 2 * kk + (lane >> 5);
-    return R * kRowBytes + ((c ^ (R & 15)) << 4);
-}
-
-// Per-lane byte offset, inside a kRot4 tile, of the transposing read that serves the A
-// operand of O^T += V^T P^T for head_dim block ddb: 16 lanes fetch a 4-token x 16-element
-// block and each lane gets one column of it (4 tokens of one head_dim index).  Add
-// (first token of the 4-token group) * 256.
-__device__ __forceinline__ int vt_piece_offset(int lane, int ddb) {
-    const int i = lane & 15, sub = (lane >> 4) & 1, half = lane >> 5;
-    const int rq = i >> 2;                              // token inside the group == (row & 3)
-    const int c = ddb * 4 + sub * 2 + ((i & 3) >> 1);
-    const int slot = (c + 4 * rq) & 15;
-    return (4 * half + rq) * kRowBytes + (slot << 4) + ((i & 1) << 3);
-}
-
-__device__ __forceinline__ bf16x8 lds_read16(const char *p) { return *(const bf16x8 *)p; }
-
-// The 8 tokens of a k-step in the order in which the accumulator of K Q^T holds them:
-// rows r0 + 4 half + {0..3} and r0 + 8 + 4 half + {0..3}.
-__device__ __forceinline__ bf16x8 lds_read_vt(const char *p) {
-    union { bf16x8 v; i16x4 h[2]; } u;
-    u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(p));
-    u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) i16x4 *)(p + 8 * kRowBytes));
-    return u.v;
-}
-
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-    const f32_2 f = {lo, hi};
-    const bf16_2 r = __builtin_convertvector(f, bf16_2);   // v_cvt_pk_bf16_f32, round to nearest even
-    return *(const uint32_t *)&r;
-}
-__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
-// Lanes l and l + 32 of a wave hold the two halves of one row (sweep 1) or token (sweep 2).  One
-// register-to-register swap of the wave's halves gives every lane both values: no trip through the LDS crossbar.
-__device__ __forceinline__ void both_halves(float x, float &lower, float &upper) {
-    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    lower = __uint_as_float(r[0]);      // the value of lane l % 32
-    upper = __uint_as_float(r[1]);      // the value of lane l % 32 + 32
-}
-__device__ __forceinline__ float halves_sum(float x) { float a, b; both_halves(x, a, b); return a + b; }
-__device__ __forceinline__ float halves_max(float x) { float a, b; both_halves(x, a, b); return fmaxf(a, b); }
-// Sum over the 32 lanes of each half of a wave, the same bits in each of them.  Lane pairings inside a row of
-// 16 through the data-parallel-primitive lane controls (neighbours, neighbouring pairs, mirror image inside 8
-// and inside 16: register to register), then the row next door.  Call with every lane active.
-template <int kCtrl>
-__device__ __forceinline__ float dpp_pair_sum(float x) {
-    return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), kCtrl, 0xf, 0xf, false));
-}
-__device__ __forceinline__ float row_sum32(float x) {      // over each half of the wave (32 lanes)
-    x = dpp_pair_sum<0xB1>(x);
-    x = dpp_pair_sum<0x4E>(x);
-    x = dpp_pair_sum<0x141>(x);
-    x = dpp_pair_sum<0x140>(x);
-    return x + __shfl_xor(x, 16);
-}
-__device__ __forceinline__ f32x16 zero16() {
-    f32x16 z;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) z[r] = 0.f;
-    return z;
-}
-
-union PiecePair { bf16x8 v; uint32_t u[4]; };
-
-// bf16 bits of -2 x for bf16 bits of x (exact: a power-of-two scaling).  The second sweep's
-// stationary o_i pieces are stored this way so that its cross-term accumulator holds
-// -2 v_p.o_i, the form the squared distances need.
-__device__ __forceinline__ uint16_t minus_twice_bf16(uint16_t bits) {
-    return (uint16_t)(__float_as_uint(-2.0f * __uint_as_float((uint32_t)bits << 16)) >> 16);
-}
-
-// Pins a value loaded from global memory as "consumed here", so that the wait for its load
-// is placed here (before the pipelined loops) and not inside them, where it would also
-// wait for the direct-to-LDS tile loads in flight.
-__device__ __forceinline__ void settle(const bf16x8 &x) { asm volatile("" ::"v"(x)); }
-__device__ __forceinline__ void settle(const float &x) { asm volatile("" ::"v"(x)); }
-
-// Interleaving recipe for one pipeline step, applied to the step's basic block: after two
-// LDS reads, repeat {1 matrix-core op, `valu` vector-ALU ops, `ds` LDS reads}.
-template <int kSlots, int kValu, int kDs>
-__device__ __forceinline__ void interleave_hint() {
-    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-#pragma unroll
-    for (int i = 0; i < kSlots; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, kValu, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, kDs, 0);
-    }
-}
 
 // ------------------------------------------------------------------------------------
 // Sweep 1
@@ -841,10 +630,10 @@ __global__ __launch_bounds__(128) void mfma_combine_hold(const uint16_t *__restr
     s_oo = row_sum32(s_oo);
     if (__any(separate)) { s_vv = row_sum32(s_vv); s_dd = row_sum32(s_dd); s_cc = row_sum32(s_cc); }
     uint2 hi_bits, lo_bits;
-    hi_bits.x = live ? (uint32_t)minus_twice_bf16(ob[0]) | ((uint32_t)minus_twice_bf16(ob[1]) << 16) : 0u;
-    hi_bits.y = live ? (uint32_t)minus_twice_bf16(ob[2]) | ((uint32_t)minus_twice_bf16(ob[3]) << 16) : 0u;
-    lo_bits.x = live ? (uint32_t)minus_twice_bf16(olo[0]) | ((uint32_t)minus_twice_bf16(olo[1]) << 16) : 0u;
-    lo_bits.y = live ? (uint32_t)minus_twice_bf16(olo[2]) | ((uint32_t)minus_twice_bf16(olo[3]) << 16) : 0u;
+    hi_bits.x = live ? (uint32_t)cross_operand_bf16(ob[0]) | ((uint32_t)cross_operand_bf16(ob[1]) << 16) : 0u;
+    hi_bits.y = live ? (uint32_t)cross_operand_bf16(ob[2]) | ((uint32_t)cross_operand_bf16(ob[3]) << 16) : 0u;
+    lo_bits.x = live ? (uint32_t)cross_operand_bf16(olo[0]) | ((uint32_t)cross_operand_bf16(olo[1]) << 16) : 0u;
+    lo_bits.y = live ? (uint32_t)cross_operand_bf16(olo[2]) | ((uint32_t)cross_operand_bf16(olo[3]) << 16) : 0u;
     *(uint2 *)(out_bf16 + crow * kD + dd) = hi_bits;
     *(uint2 *)(out_bf16 + lo_plane + crow * kD + dd) = lo_bits;
     if (sub != 0) return;
@@ -858,7 +647,7 @@ __global__ __launch_bounds__(128) void mfma_combine_hold(const uint16_t *__restr
     }
     const float a2 = a * a;
     row_const[crow * 4 + 0] = 2.0f * (T * c2 + log2f(ltot));   // A_ip^2 = exp2(2 log2e Z_ip - this)
-    row_const[crow * 4 + 1] = s_oo;                            // ||o^_i||^2
+    row_const[crow * 4 + 1] = s_oo * kCrossScale;              // ||o^_i||^2 / 128
     row_const[crow * 4 + 2] = __int_as_float(len - W + (row % W));
     row_const[crow * 4 + 3] = 0.f;
     special[crow * 4 + 0] = __int_as_float(separate ? c_tok : -1);
@@ -872,28 +661,6 @@ __global__ __launch_bounds__(128) void mfma_combine_hold(const uint16_t *__restr
 // ------------------------------------------------------------------------------------
 // Sweep 2
 // ------------------------------------------------------------------------------------
-// Sum of squares of the 8 bf16 values in a 16-byte operand piece.
-__device__ __forceinline__ float sumsq8(const bf16x8 x, float acc) {
-    union { bf16x8 v; bf16x2 h[4]; } u;
-    u.v = x;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) acc = __builtin_amdgcn_fdot2_f32_bf16(u.h[e], u.h[e], acc, false);
-    return acc;
-}
-
-// Sum of the absolute values of the 8 bf16 values in a 16-byte operand piece: each pair is
-// dotted with (+-1, +-1) carrying the pair's own signs.
-__device__ __forceinline__ float sumabs8(const bf16x8 x, float acc) {
-    union { bf16x8 v; uint32_t u[4]; bf16x2 h[4]; } in, sg;
-    in.v = x;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        sg.u[e] = (in.u[e] & 0x80008000u) | 0x3f803f80u;
-        acc = __builtin_amdgcn_fdot2_f32_bf16(in.h[e], sg.h[e], acc, false);
-    }
-    return acc;
-}
-
 struct Sweep2Regs {
     bf16x8 q[8], ohi[8], olo[8];   // stationary A operands of this wave's row block
     float c_m2[16], c_oo[16];      // per accumulator register: 2 (max + log2 sum), ||o^||^2 of its row
@@ -977,17 +744,18 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int i = wave * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                if (tokx == excl_i[i]) z[r] = -1e15f;
+                if (tokx == excl_i[i]) z[r] = kHiddenLogit;
             }
         }
         // ---- vector ALUs ----
-        // vo holds -2 v_p.o^_i (the stationary pieces are stored pre-scaled by -2, an exact
-        // scaling), so with w = ||v_p - o^_i||^2 = (||v_p||^2 + ||o^_i||^2) + vo:
-        //   Eq. 5 term  A^2 Z^2 w
+        // vo holds -2 v_p.o^_i / 128 and c_oo holds ||o^_i||^2 / 128 (see kCrossScale), so with
+        // w7 = ||v_p - o^_i||^2 / 128 = (||v_p||^2 / 128 + c_oo) + vo and z the raw dot product (Z = z / sqrt(128)):
+        //   Eq. 5 term  A^2 Z^2 w = A^2 z^2 w7
         //   Eq. 6 term  A^2 ||(1+Z) v - Z o^||^2 = A^2 (||v||^2 + Z (2 (||v||^2 - v.o^) + Z w))
+        //                                        = A^2 (||v||^2 + z (2 ||v||^2 / sqrt(128) + sqrt(128) vo + z w7))
         // Rounding can leave a term a hair below zero; the sums are clamped once at the end.
         const int tok = t_begin + n * 32 + (lane & 31);
-        const float vv2 = vv + vv;
+        const float vv7 = vv * kCrossScale, vv2s = vv * (2.0f * kInvSqrtD);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             // A_ip^2, or A_ip itself (half the exponent) for the attention-only scores
@@ -999,12 +767,11 @@ __device__ __forceinline__ void sweep2_step(Sweep2Regs &R, const char *smem, uin
             }
             if (kDoV || kDoA) acc_v += a2;
             if (kNeedVO) {
-                const float zz = z[r] * kInvSqrtD;                                // Z_ip
-                const float w = (vv + R.c_oo[r]) + vo[r];                         // ||v_p - o^_i||^2
-                if (kDoK) acc_k = fmaf(a2 * zz * zz, w, acc_k);
+                const float w7 = (vv7 + R.c_oo[r]) + vo[r];                       // ||v_p - o^_i||^2 / 128
+                if (kDoK) acc_k = fmaf(a2 * z[r] * z[r], w7, acc_k);
                 if (kDoJ) {
-                    const float h = fmaf(zz, w, vv2 + vo[r]);
-                    acc_j = fmaf(a2, fmaf(zz, h, vv), acc_j);
+                    const float h = fmaf(z[r], w7, fmaf(vo[r], kSqrtD, vv2s));
+                    acc_j = fmaf(a2, fmaf(z[r], h, vv), acc_j);
                 }
             }
         }
@@ -1237,12 +1004,16 @@ hipError_t launch_sweep2(const ScoreArgs &a, const ScoreWorkspace &ws, char *bas
     float *dst = ws.n_chunks > 1 ? (float *)(base + ws.planes) : a.scores;
     const size_t chunk_stride = ws.n_chunks > 1 ? plane_elems * nv : 0;
     const dim3 grid((a.N + ws.range_len - 1) / ws.range_len, ws.n_chunks, a.B * a.Hkv);
-    mfma_sweep2<kVariant><<<grid, dim3(kThreads), 0, stream>>>(
-        (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens,
-        ws.range_len, ws.m_pad, (const uint16_t *)(base + ws.out_bf16), (const float *)(base + ws.row_const),
-        (const float *)(base + ws.special), dst, plane_elems, chunk_stride,
-        ws.n_chunks == 1 ? a.accumulate : 0);
-    e = hipGetLastError();
+    if (ws.use_wide) {
+        e = launch_sweep2_wide(a, ws, base, dst, plane_elems, chunk_stride, stream);
+    } else {
+        mfma_sweep2<kVariant><<<grid, dim3(kThreads), 0, stream>>>(
+            (const uint16_t *)a.q, (const uint16_t *)a.k, (const uint16_t *)a.v, a.N, a.W, a.Hq, a.Hkv, a.ragged, a.lens,
+            ws.range_len, ws.m_pad, (const uint16_t *)(base + ws.out_bf16), (const float *)(base + ws.row_const),
+            (const float *)(base + ws.special), dst, plane_elems, chunk_stride,
+            ws.n_chunks == 1 ? a.accumulate : 0);
+        e = hipGetLastError();
+    }
     if (e != hipSuccess || ws.n_chunks == 1) return e;
     const size_t total = plane_elems * nv;
     mfma_sum_planes<<<dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream>>>(dst, ws.n_chunks, chunk_stride, total, a.scores,
@@ -1263,10 +1034,14 @@ void mfma_plan(int B, int N, int W, int Hq, int Hkv, int d, int variant, ScoreWo
     if (const int v = tuned_splits(); v >= 1 && v <= max_splits) splits = v;    // obc_set_score_tuning
     ws->split_len = ((N + splits - 1) / splits + kTileTok - 1) / kTileTok * kTileTok;
     ws->splits = (N + ws->split_len - 1) / ws->split_len;
-    // Token range of one sweep-2 block: about two blocks per compute unit over the whole launch.
+    // Token range of one sweep-2 block: about two blocks per compute unit over the whole launch; the
+    // register-blocked form runs one workgroup per compute unit and gets one block each.
+    const int form = tuned_sweep2_form();
+    ws->use_wide = (form != 1 && sweep2_wide_covers(variant, ws->m_pad, (Hq / Hkv) * W)) ? 1 : 0;
     {
         const long long units = (long long)N * BH * ws->n_chunks;
-        long long r = ((units + 511) / 512 + 63) / 64 * 64;
+        const long long blocks = ws->use_wide ? 256 : 512;
+        long long r = ((units + blocks - 1) / blocks + 63) / 64 * 64;
         ws->range_len = (int)(r < 128 ? 128 : (r > 8192 ? 8192 : r));
     }
     if (const int v = tuned_range(); v >= 64 && v <= 65536 && v % 64 == 0) ws->range_len = v;

@@ -26,3 +26,4 @@ def score_path():
     yield obc.obc_set_score_path
     obc.obc_set_score_path("auto")
     obc.obc_set_score_tuning(0, 0)
+    obc.obc_set_sweep2_form(0)

@@ -25,6 +25,15 @@ def test_score_select_compact_match_oracle(name):
     print(name, {k: "%.2e" % v for k, v in worst.items()})
 
 
+@pytest.mark.parametrize("name", ["s_bf16_llama", "s_bf16_ragged", "s_bf16_strong_sink", "s_bf16_tiny", "s_bf16_max_rows",
+                                  "c2_llama8b_8k"])
+def test_narrow_second_sweep_matches_oracle_too(name, score_path):
+    """Shapes whose second sweep runs 64 rows per wave by default, forced through the 32-rows-per-wave kernel."""
+    obc.obc_set_sweep2_form(1)
+    worst = _run_case(CASES[name])
+    print(name, {k: "%.2e" % v for k, v in worst.items()})
+
+
 def test_deterministic_bits():
     wl = CASES["s_bf16_llama"]
     dev = to_device(synth.make_inputs(wl))
