@@ -152,6 +152,8 @@ int obc_oracle_window_attention(const double *q, const double *k, const double *
  *                 the completed square of Eq. 6 (expanding it gives
  *                 ||v||^2 + Z^2 ||v-o||^2 + 2 Z (||v||^2 - v.o)).
  * joint_form = 1: Eq. 6 literally: S^value + S^key + 2 sum A^2 Z (||v||^2 - v.o).
+ * joint_form + 2 (test only): every key, the row's largest-weight one included, takes the plain differences
+ *                 v_p - o_i; the tests compare this with the default where fp64 resolves both.
  */
 int obc_oracle_score(const double *q, const double *k, const double *v,
                      int B, int Hq, int Hkv, int N, int W, int d,
@@ -204,7 +206,7 @@ int obc_oracle_score(const double *q, const double *k, const double *v,
             for (int p = 0; p < n_vis; ++p) {
                 const double *vp = Vg + (size_t)p * d;
                 const double A2 = a[p] * a[p];
-                const int top = p == p_top;
+                const int top = p == p_top && !(joint_form & 2);
                 double vv = 0.0, vmo2 = 0.0, vvmvo = 0.0, sq = 0.0;
                 for (int j = 0; j < d; ++j) {
                     const double diff = top ? dtop[j] : vp[j] - o[j];
@@ -237,7 +239,7 @@ int obc_oracle_score(const double *q, const double *k, const double *v,
             const int live = p < len;
             if (s_value) s_value[idx] = live ? sv : 0.0;
             if (s_key) s_key[idx] = live ? sk : 0.0;
-            if (s_joint) s_joint[idx] = live ? (joint_form ? sv + sk + sx : sj) : 0.0;
+            if (s_joint) s_joint[idx] = live ? ((joint_form & 1) ? sv + sk + sx : sj) : 0.0;
         }
     }
     free(hv); free(hk); free(hj); free(hx);

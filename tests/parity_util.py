@@ -41,6 +41,21 @@ def score_error(gpu: np.ndarray, ref: np.ndarray, budget: int, lens, tol: float)
     return worst, where
 
 
+def raw_relative_error(gpu: np.ndarray, ref: np.ndarray, lens):
+    """(max, 99.9th percentile) of |gpu - ref| / |ref| over the live head-tokens with a nonzero oracle score: no floor.
+    Reported beside the floored error, not asserted (scores far below the selection threshold may sit at the edge of
+    what fp32 resolves)."""
+    B, H, N = ref.shape
+    errs = []
+    for b in range(B):
+        L = N if lens is None else lens[b]
+        r = ref[b, :, :L]
+        nz = r != 0
+        errs.append((np.abs(gpu[b, :, :L] - r)[nz] / np.abs(r[nz])).ravel())
+    e = np.concatenate(errs)
+    return (float(e.max()), float(np.quantile(e, 0.999))) if e.size else (0.0, 0.0)
+
+
 def check_selection_against_oracle_scores(keep: np.ndarray, ref: np.ndarray, budget: int, lens, tol: float):
     """End-to-end index parity: outside a band of +-2*tol around the head's budget-th
     largest oracle score the kept set is unique; inside it either choice is valid."""

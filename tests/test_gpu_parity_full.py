@@ -1,7 +1,10 @@
 """GPU parity at the benchmark's full sizes (configs c3, c4, c5), in the launch configuration
-bench.py times.  The fp64 oracle scores a sample of KV heads in full; every head is checked
-through properties that hold at any size (finite, non-negative, zero padding, selection
-bit-exact against the oracle's select on the same fp32 scores, byte-exact compaction)."""
+bench.py times.  The fp64 oracle scores EVERY (sequence, KV head) of c3 and c4 and of eight of
+c5's 32 layers (the first and the last among them) in full, element by element; the attention-sink
+variant of c3 is compared on two heads.  Every head is also checked through properties that hold
+at any size (finite, non-negative, zero padding, selection bit-exact against the oracle's select
+on the same fp32 scores, byte-exact compaction).  The worst raw relative error (no floor) is
+printed per variant."""
 import numpy as np
 import pytest
 import torch
@@ -11,22 +14,9 @@ from paper_2510_07651_amd import binding as obc
 from paper_2510_07651_amd import synth
 
 from parity_util import (TOL, check_keep_idx_valid, check_selection_against_oracle_scores, oracle_scores,
-                         score_error, to_device)
+                         raw_relative_error, score_error, to_device)
 
 pytestmark = pytest.mark.gpu
-
-
-def _check_heads(wl, x, gpu_scores, heads, variant_idx):
-    """gpu_scores: [B,Hkv,N] numpy of one variant; oracle on the sampled (b, g) heads."""
-    tol = TOL[wl.dtype]
-    refs = oracle_scores(x, heads)
-    worst = 0.0
-    for (b, g), ref3 in zip(heads, refs):
-        lens = None if x["seq_lens"] is None else [x["seq_lens"][b]]
-        err, where = score_error(gpu_scores[b:b + 1, g:g + 1], ref3[variant_idx], wl.budget, lens, tol)
-        assert err <= tol, "%s head (%d,%d): err %.3g at %s" % (wl.name, b, g, err, where)
-        worst = max(worst, err)
-    return worst, refs
 
 
 def _pipeline_checks(wl, x, dev, scores_t):
@@ -47,18 +37,30 @@ def _pipeline_checks(wl, x, dev, scores_t):
     return keep_np
 
 
+def _check_all_heads(wl, x, gpu_by_variant, keep_by_variant):
+    """Every head against the oracle: floored error within tolerance, raw error printed, kept sets consistent with the
+    oracle's own scores outside the tolerance band.  gpu_by_variant: {variant index: [B,Hkv,N] numpy}."""
+    tol = TOL[wl.dtype]
+    lens = x["seq_lens"]
+    ref = oracle.score(x["q"], x["k"], x["v"], seq_lens=lens)          # [3, B, Hkv, N] fp64, all heads
+    for vi, g_np in gpu_by_variant.items():
+        err, where = score_error(g_np, ref[vi], wl.budget, lens, tol)
+        assert err <= tol, "%s %s: err %.3g at %s" % (wl.name, synth.VARIANTS[vi], err, where)
+        raw_max, raw_p999 = raw_relative_error(g_np, ref[vi], lens)
+        in_band = check_selection_against_oracle_scores(keep_by_variant[vi], ref[vi], wl.budget, lens, tol)
+        print("%s %s: all %d heads, worst error %.2e (floored), raw relative error max %.2e p99.9 %.2e, %d tokens in "
+              "the +-2 tol band around the thresholds" % (wl.name, synth.VARIANTS[vi], g_np.shape[0] * g_np.shape[1], err,
+                                                          raw_max, raw_p999, in_band))
+
+
 def test_c3_llama_b4_32k_joint():
     wl = synth.config("c3")
     x = synth.make_inputs(wl)
     dev = to_device(x)
     s = obc.obc_score(dev["q"], dev["k"], dev["v"], "joint")
     torch.cuda.synchronize()
-    heads = [(0, 0), (2, 5), (3, 7)]
-    worst, refs = _check_heads(wl, x, s.cpu().numpy(), heads, 2)
     keep_np = _pipeline_checks(wl, x, dev, s)
-    for (b, g), ref3 in zip(heads, refs):
-        check_selection_against_oracle_scores(keep_np[b:b + 1, g:g + 1], ref3[2], wl.budget, None, TOL[wl.dtype])
-    print("c3 worst sampled error %.2e" % worst)
+    _check_all_heads(wl, x, {2: s.cpu().numpy()}, {2: keep_np})
 
 
 @pytest.mark.parametrize("sink_gain", [3.0, 1.0])
@@ -90,21 +92,14 @@ def test_c4_qwen_128k_all_variants():
     dev = to_device(x)
     s = obc.obc_score(dev["q"], dev["k"], dev["v"], "all")
     torch.cuda.synchronize()
-    heads = [(0, 2)]
-    refs = oracle_scores(x, heads)
-    for vi, name in enumerate(synth.VARIANTS):
-        g_np = s[vi].cpu().numpy()
-        for (b, g), ref3 in zip(heads, refs):
-            err, where = score_error(g_np[b:b + 1, g:g + 1], ref3[vi], wl.budget, None, TOL[wl.dtype])
-            assert err <= TOL[wl.dtype], "c4 %s: err %.3g at %s" % (name, err, where)
-            print("c4", name, "sampled head error %.2e" % err)
-        keep_np = _pipeline_checks(wl, x, dev, s[vi].contiguous())
-        for (b, g), ref3 in zip(heads, refs):
-            check_selection_against_oracle_scores(keep_np[b:b + 1, g:g + 1], ref3[vi], wl.budget, None,
-                                                  TOL[wl.dtype])
+    gpu, keeps = {}, {}
+    for vi in range(3):
+        gpu[vi] = s[vi].cpu().numpy()
+        keeps[vi] = _pipeline_checks(wl, x, dev, s[vi].contiguous())
+    _check_all_heads(wl, x, gpu, keeps)
 
 
-@pytest.mark.parametrize("layer", [0, 31])
+@pytest.mark.parametrize("layer", [0, 4, 9, 13, 18, 22, 27, 31])
 def test_c5_ragged_layers(layer):
     wl = synth.config("c5")
     x = synth.make_inputs(wl, layer=layer)
@@ -112,10 +107,6 @@ def test_c5_ragged_layers(layer):
     lens = x["seq_lens"]
     s = obc.obc_score(dev["q"], dev["k"], dev["v"], "joint", seq_lens=lens)
     torch.cuda.synchronize()
-    heads = [(0, 3), (1, 6)]
-    worst, refs = _check_heads(wl, x, s.cpu().numpy(), heads, 2)
     keep_np = _pipeline_checks(wl, x, dev, s)
-    for (b, g), ref3 in zip(heads, refs):
-        check_selection_against_oracle_scores(keep_np[b:b + 1, g:g + 1], ref3[2], wl.budget, [lens[b]],
-                                              TOL[wl.dtype])
-    print("c5 layer", layer, "lens", lens, "worst sampled error %.2e" % worst)
+    print("c5 layer", layer, "lens", lens)
+    _check_all_heads(wl.with_(name="%s[layer %d]" % (wl.name, layer)), x, {2: s.cpu().numpy()}, {2: keep_np})

@@ -2,7 +2,9 @@
 
 Every draw stays inside the documented limits of the C ABI (W <= 64, G*W <= 512, W <= len_b <= N, budget <= len_b);
 the comparison is the one of test_gpu_parity_small: scores within the dtype's tolerance of the fp64 oracle, kept
-indices bit-exact given the same fp32 scores.
+indices bit-exact given the same fp32 scores.  The budget of every draw is one eighth of the shortest sequence (the
+regime of the paper's 10-40 % budgets): the comparison floor is tied to the budget-th largest score, and a tiny budget
+would lift that floor to the scale of a head's top scores.
 """
 import numpy as np
 import pytest
@@ -31,7 +33,7 @@ def _draw(seed, decode=False):
     room = min_len - W - sinks
     needles = int(rng.integers(0, min(6, room) + 1)) if room > 8 and rng.random() < 0.4 else 0
     return synth.Workload("rnd%d" % seed, B=B, Hq=G * Hkv, Hkv=Hkv, d=d, N=N, W=W, dtype=dtype,
-                          budget=int(rng.integers(1, min_len + 1)), seed=7000 + seed, sinks=sinks,
+                          budget=max(1, min_len // 8), seed=7000 + seed, sinks=sinks,
                           outlier_channels=int(rng.integers(0, 5)), needles=needles, ragged=ragged,
                           pad_nan=bool(ragged) and rng.random() < 0.5,
                           shared_query=float(rng.choice([0.0, 0.0, 0.5, 1.0])))
@@ -60,7 +62,7 @@ def _draw_long(seed):
     min_len = ragged[0] if ragged else N
     sinks = int(rng.integers(0, 5))
     return synth.Workload("long%d" % seed, B=B, Hq=G * Hkv, Hkv=Hkv, d=128, N=N, W=W, dtype="bf16",
-                          budget=int(rng.integers(1, min_len + 1)), seed=9500 + seed, sinks=sinks,
+                          budget=max(1, min_len // 8), seed=9500 + seed, sinks=sinks,
                           outlier_channels=int(rng.integers(0, 5)), needles=int(rng.integers(0, 9)), ragged=ragged,
                           pad_nan=bool(ragged) and rng.random() < 0.5,
                           shared_query=float(rng.choice([0.0, 0.0, 0.5, 1.0])))

@@ -569,44 +569,106 @@ def test_compact_pads_negative_indices_with_zero_rows():
     assert np.all(ko[0, 0, 3:] == 0) and np.all(ko[0, 1, 1:] == 0) and np.all(vo[0, 1, 1:] == 0)
 
 
+def _fifty_digit_scores(mp, qn, kn, vn, lens):
+    """Eq. 4-6 term by term in 50-digit arithmetic, window sum (Eq. 9) and sum over the group's query heads
+    (Appendix A.5): per (sequence, KV head, token) the three scores, and the least 1 - max_p A_ip over all rows."""
+    B, Hq, W, d = qn.shape
+    Hkv, N = kn.shape[1], kn.shape[2]
+    G = Hq // Hkv
+    M = lambda a: [mp.mpf(float(x)) for x in a]
+    ref = {name: [[[mp.mpf(0)] * N for _ in range(Hkv)] for _ in range(B)] for name in ("value", "key", "joint")}
+    least_rest, most_rest = mp.mpf(1), mp.mpf(0)
+    for b in range(B):
+        L = N if lens is None else lens[b]
+        for h in range(Hq):
+            g = h // G
+            for r in range(W):
+                n_vis = L - W + r + 1
+                z = [sum(a * c for a, c in zip(M(qn[b, h, r]), M(kn[b, g, p]))) / mp.sqrt(d) for p in range(n_vis)]
+                zmax = max(z)
+                e = [mp.exp(x - zmax) for x in z]
+                tot = sum(e)
+                A = [x / tot for x in e]
+                least_rest = min(least_rest, 1 - max(A))
+                most_rest = max(most_rest, 1 - max(A))
+                o = [sum(A[p] * mp.mpf(float(vn[b, g, p, j])) for p in range(n_vis)) for j in range(d)]
+                for p in range(n_vis):
+                    vp = M(vn[b, g, p])
+                    ref["value"][b][g][p] += A[p] ** 2 * sum(x * x for x in vp)
+                    ref["key"][b][g][p] += A[p] ** 2 * z[p] ** 2 * sum((x - y) ** 2 for x, y in zip(vp, o))
+                    ref["joint"][b][g][p] += A[p] ** 2 * sum(((1 + z[p]) * x - z[p] * y) ** 2 for x, y in zip(vp, o))
+    return ref, least_rest, most_rest
+
+
+FIFTY_DIGIT_SHAPES = {
+    # name: (B, Hq, Hkv, N, W, d, true lengths)
+    "mha_pair": (1, 2, 1, 24, 2, 8, None),
+    "gqa4_w5_ragged_d16": (2, 8, 2, 40, 5, 16, [40, 29]),
+}
+
+
+@pytest.mark.parametrize("shape", list(FIFTY_DIGIT_SHAPES))
 @pytest.mark.parametrize("gain", [2.0, 4.0, 6.0, 8.0])
-def test_scores_of_a_key_that_takes_nearly_all_attention_match_50_digit_arithmetic(gain):
+def test_scores_of_a_key_that_takes_nearly_all_attention_match_50_digit_arithmetic(gain, shape):
     """Eq. 4-6 evaluated term by term in 50-digit arithmetic (mpmath) from the same inputs.  One key is aligned with
     every window query, so that it holds 1 - 1e-4 .. 1 - 1e-16 of each row's weight and v_p - o_i is the difference of
-    two nearly equal vectors: plain fp64 loses eps / (1 - A) of that difference, the oracle must not."""
-    mp = pytest.importorskip("mpmath")
+    two nearly equal vectors: plain fp64 loses eps / (1 - A) of that difference, the oracle must not.  Shapes: two
+    query heads on one KV head; and a group of four query heads per KV head, a five-row window, a ragged batch and
+    head_dim 16 (group sum, row-wise causal mask and padding all in play)."""
+    import mpmath as mp                                   # (a plain import: without the module this pin must fail, not skip)
     mp.mp.dps = 50
+    B, Hq, Hkv, N, W, d, lens = FIFTY_DIGIT_SHAPES[shape]
     g = torch.Generator().manual_seed(91)
-    B, Hq, Hkv, N, W, d = 1, 2, 1, 24, 2, 8
     q = torch.randn(B, Hq, W, d, generator=g, dtype=torch.float64)
     k = torch.randn(B, Hkv, N, d, generator=g, dtype=torch.float64)
     v = torch.randn(B, Hkv, N, d, generator=g, dtype=torch.float64)
     u = torch.randn(d, generator=g, dtype=torch.float64)
     q = q + 3.0 * u / u.norm() * d ** 0.5              # a direction all queries share
-    k[0, 0, 5] = gain * u / u.norm() * d ** 0.5         # key 5 points along it
+    k[:, :, 5] = gain * u / u.norm() * d ** 0.5         # key 5 of every head points along it
     qn, kn, vn = q.numpy(), k.numpy(), v.numpy()
-    sv, sk, sj = oracle.score(qn, kn, vn)
-    _, _, sj_literal = oracle.score(qn, kn, vn, joint_form=1)
-    M = lambda a: [mp.mpf(float(x)) for x in a]
-    ref = {"value": [mp.mpf(0)] * N, "key": [mp.mpf(0)] * N, "joint": [mp.mpf(0)] * N}
-    least_rest = mp.mpf(1)
-    for h in range(Hq):
-        for r in range(W):
-            n_vis = N - W + r + 1
-            z = [sum(a * b for a, b in zip(M(qn[0, h, r]), M(kn[0, 0, p]))) / mp.sqrt(d) for p in range(n_vis)]
-            zmax = max(z)
-            e = [mp.exp(x - zmax) for x in z]
-            tot = sum(e)
-            A = [x / tot for x in e]
-            least_rest = min(least_rest, 1 - max(A))
-            o = [sum(A[p] * mp.mpf(float(vn[0, 0, p, j])) for p in range(n_vis)) for j in range(d)]
-            for p in range(n_vis):
-                vp = M(vn[0, 0, p])
-                ref["value"][p] += A[p] ** 2 * sum(x * x for x in vp)
-                ref["key"][p] += A[p] ** 2 * z[p] ** 2 * sum((x - y) ** 2 for x, y in zip(vp, o))
-                ref["joint"][p] += A[p] ** 2 * sum(((1 + z[p]) * x - z[p] * y) ** 2 for x, y in zip(vp, o))
+    sv, sk, sj = oracle.score(qn, kn, vn, seq_lens=lens)
+    _, _, sj_literal = oracle.score(qn, kn, vn, seq_lens=lens, joint_form=1)
+    ref, least_rest, _ = _fifty_digit_scores(mp, qn, kn, vn, lens)
     assert least_rest < mp.mpf(10) ** (-2 * gain + 1), "the case must be as lopsided as it claims (1 - A = %s)" % least_rest
     for name, got in (("value", sv), ("key", sk), ("joint", sj), ("joint", sj_literal)):
-        for p in range(N):
-            want = ref[name][p]
-            assert abs(mp.mpf(float(got[0, 0, p])) - want) <= mp.mpf("1e-9") * want, (name, p, float(got[0, 0, p]), float(want))
+        for b in range(B):
+            L = N if lens is None else lens[b]
+            for h in range(Hkv):
+                for p in range(N):
+                    want = ref[name][b][h][p] if p < L else mp.mpf(0)
+                    assert abs(mp.mpf(float(got[b, h, p])) - want) <= mp.mpf("1e-9") * want, (name, b, h, p, float(got[b, h, p]), float(want))
+
+
+@pytest.mark.parametrize("gain", [0.26, 0.29, 0.32])
+def test_largest_weight_branch_agrees_with_the_plain_branch_where_fp64_resolves_both(gain):
+    """The oracle forms v_p - o_i of each row's largest-weight key as sum_q A_iq (v_p - v_q) (Section 3: a softmax row
+    sums to one) and of every other key as the plain difference.  Where the largest weight is moderate (0.2 .. 0.6 of
+    the row) fp64 resolves both forms: the same C function with the special case switched off (test-only flag) must
+    then agree to 1e-12 on every token, for all three scores and both joint forms; and the 50-digit evaluation sits
+    beside both."""
+    import mpmath as mp
+    mp.mp.dps = 50
+    B, Hq, Hkv, N, W, d, lens = 2, 8, 2, 40, 5, 16, [40, 29]
+    g = torch.Generator().manual_seed(92)
+    q = torch.randn(B, Hq, W, d, generator=g, dtype=torch.float64)
+    k = torch.randn(B, Hkv, N, d, generator=g, dtype=torch.float64)
+    v = torch.randn(B, Hkv, N, d, generator=g, dtype=torch.float64)
+    u = torch.randn(d, generator=g, dtype=torch.float64)
+    q = 0.3 * q + 3.0 * u / u.norm() * d ** 0.5
+    k = 0.3 * k
+    k[:, :, 7] = gain * u / u.norm() * d ** 0.5
+    qn, kn, vn = q.numpy(), k.numpy(), v.numpy()
+    _, A, _ = oracle.window_attention(qn, kn, vn, seq_lens=lens)
+    top = np.nanmax(np.where(np.isfinite(A), A, np.nan), axis=-1)
+    assert top.min() > 0.2 and top.max() < 0.6, (top.min(), top.max())     # the case is what it claims
+    ref, _, _ = _fifty_digit_scores(mp, qn, kn, vn, lens)
+    for form in (0, 1):
+        special = oracle.score(qn, kn, vn, seq_lens=lens, joint_form=form)
+        plain = oracle.score(qn, kn, vn, seq_lens=lens, joint_form=form + 2)
+        for name, a, b_ in zip(("value", "key", "joint"), special, plain):
+            np.testing.assert_allclose(a, b_, rtol=1e-12, atol=0.0, err_msg="%s form %d" % (name, form))
+            for b in range(B):
+                for h in range(Hkv):
+                    for p in range(lens[b]):
+                        want = ref[name][b][h][p]
+                        assert abs(mp.mpf(float(a[b, h, p])) - want) <= mp.mpf("1e-11") * want, (name, form, b, h, p)
