@@ -258,6 +258,29 @@ int obc_compact_inplace(void *k, void *v, float *scores, const int32_t *keep_idx
                         int B, int Hkv, int N, int budget, int d, int dtype, void *hip_stream);
 
 /*
+ * One decoding step in one call (Section 4.2, closing remark: scores accumulate over the decoding steps; Appendix C,
+ * decoding setup: an eviction decision at every step, the first tokens kept as attention sinks and the most recent
+ * ones kept as well; Appendix D asks for specialised kernels for score computation and cache eviction).  Equivalent
+ * to, on the same stream,
+ *   obc_score_accumulate(q, k, v, W = 1, ...)                          the new token's query row against len_b rows,
+ *   obc_select_protected(num_hh = len_b - 1 - num_sinks - num_recent)  every competing token but one is kept,
+ *   obc_compact_inplace(k, v, scores, that list)                       the gap is closed in place,
+ * without forming the index lists: per (b, KV head) the dropped token is the one with the lowest running score among
+ * num_sinks <= p < len_b - num_recent, the highest index among equal scores (selection lets the lower index win a
+ * tie; -0 equals +0, NaN ranks lowest); rows and scores after it move down by one and scores[len_b - 1 .. N) become 0.
+ *   q        [B, Hq, 1, d]    k, v  [B, Hkv, N, d], updated in place (row len_b - 1 keeps a stale copy)
+ *   scores   [B, Hkv, N] fp32 running scores, updated in place
+ *   evicted  [B, Hkv] int32 (device) receives the dropped positions; may be NULL
+ *   variant  any single score (not OBC_ALL)
+ * Requires num_sinks + num_recent < len_b for every sequence and a workspace of obc_decode_step_workspace_bytes(...)
+ * bytes, 256-byte aligned.  Argument errors are found before anything is launched.
+ */
+int obc_decode_step_workspace_bytes(int B, int N, int Hq, int Hkv, int d, int dtype, int variant, size_t *bytes_out);
+int obc_decode_step(const void *q, void *k, void *v, float *scores, int32_t *evicted,
+                    int N, int Hq, int Hkv, int d, int variant, int B, int dtype, const int32_t *seq_lens_host,
+                    int num_sinks, int num_recent, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Running scores follow their tokens through an eviction (Section 4.2, closing remark, and
  * Appendix C, decoding setup: scores accumulate over time and an eviction is made at every
  * step, so a kept token keeps its accumulated score):

@@ -83,6 +83,11 @@ def load_library():
     lib.obc_score_static.restype = c_int
     lib.obc_score_static.argtypes = [c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int, c_int, c_void_p,
                                      c_int, c_int, i32p, c_int, c_void_p]
+    lib.obc_decode_step_workspace_bytes.restype = c_int
+    lib.obc_decode_step_workspace_bytes.argtypes = [c_int] * 7 + [ctypes.POINTER(c_size_t)]
+    lib.obc_decode_step.restype = c_int
+    lib.obc_decode_step.argtypes = [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int, c_int, c_int, c_int, c_int,
+                                    c_int, c_int, i32p, c_int, c_int, c_void_p, c_size_t, c_void_p]
     lib.obc_set_score_path.restype = c_int
     lib.obc_set_score_path.argtypes = [c_int]
     lib.obc_set_score_tuning.restype = c_int
@@ -383,6 +388,39 @@ def obc_compact_inplace(k: torch.Tensor, v: torch.Tensor, keep_idx: torch.Tensor
                                             _dtype_code(k), _stream_ptr(k))
     if rc != OBC_OK:
         raise ObcError(rc, "obc_compact_inplace")
+
+
+def obc_decode_step_workspace_bytes(B, N, Hq, Hkv, d, dtype, variant) -> int:
+    out = ctypes.c_size_t(0)
+    rc = load_library().obc_decode_step_workspace_bytes(B, N, Hq, Hkv, d, dtype, variant, ctypes.byref(out))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_decode_step_workspace_bytes")
+    return int(out.value)
+
+
+def obc_decode_step(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, scores: torch.Tensor, variant="joint",
+                    num_sinks: int = 0, num_recent: int = 0, seq_lens=None, evicted: Optional[torch.Tensor] = None,
+                    workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Accumulates the new row's scores, drops the lowest-scored unprotected token of every head and closes the gap in
+    k, v and scores, all in place.  Returns the dropped positions [B,Hkv] int32."""
+    _require_cuda(q, k, v, scores)
+    B, Hq, W, d = q.shape
+    _, Hkv, N, _ = k.shape
+    if W != 1 or v.shape != k.shape or tuple(scores.shape) != (B, Hkv, N) or scores.dtype != torch.float32:
+        raise ValueError("q must be [B,Hq,1,d], k, v [B,Hkv,N,d], scores [B,Hkv,N] float32")
+    var = VARIANT_CODES[variant] if isinstance(variant, str) else int(variant)
+    dt = _dtype_code(q)
+    if workspace is None:
+        workspace = torch.empty(obc_decode_step_workspace_bytes(B, N, Hq, Hkv, d, dt, var), dtype=torch.uint8, device=q.device)
+    if evicted is None:
+        evicted = torch.empty((B, Hkv), dtype=torch.int32, device=q.device)
+    _require_cuda(evicted, workspace)
+    rc = load_library().obc_decode_step(q.data_ptr(), k.data_ptr(), v.data_ptr(), scores.data_ptr(), evicted.data_ptr(), N,
+                                        Hq, Hkv, d, var, B, dt, _lens_arg(seq_lens, B), int(num_sinks), int(num_recent),
+                                        workspace.data_ptr(), workspace.numel(), _stream_ptr(q))
+    if rc != OBC_OK:
+        raise ObcError(rc, "obc_decode_step")
+    return evicted
 
 
 def obc_compact_scores(scores: torch.Tensor, keep_idx: torch.Tensor, n_out: Optional[int] = None,

@@ -131,6 +131,98 @@ __global__ __launch_bounds__(kMoveThreads) void move_rows_in_place(uint4 *__rest
     }
 }
 
+// ------------------------------------------------------------------------------------
+// Evict-one (the decoding setup of Appendix C: an eviction decision at every step, the first tokens kept as
+// attention sinks, the most recent ones kept as well).
+// ------------------------------------------------------------------------------------
+// Same order as the selection kernels use: larger score <=> larger key, -0 folded onto +0, NaN lowest.
+__device__ __forceinline__ uint32_t evict_order_key(float f) {
+    uint32_t u = __float_as_uint(f);
+    if (f != f) return 0u;
+    if (u == 0x80000000u) u = 0u;
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// One workgroup per (sequence, KV head): the token a protected selection of all but one competing token would drop,
+// i.e. the lowest score among first <= p < len - tail, the highest index among equal scores (the kept ones win ties
+// by the lower index).  Packed as (key, ~index) so that one unsigned minimum decides both.
+__global__ __launch_bounds__(256) void evict_pick(const float *__restrict__ scores, int N, int Hkv, int ragged,
+                                                  SeqLens lens, int first, int tail, int32_t *__restrict__ evicted) {
+    __shared__ unsigned long long best_w[4];
+    const int bg = blockIdx.x;
+    const int len = seq_len_of(lens, ragged, bg / Hkv, N);
+    const float *s = scores + (size_t)bg * N;
+    unsigned long long best = ~0ull;
+    for (int p = first + threadIdx.x; p < len - tail; p += 256) {
+        const unsigned long long cand = ((unsigned long long)evict_order_key(s[p]) << 32) | (uint32_t)~p;
+        best = cand < best ? cand : best;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const unsigned long long o = __shfl_xor(best, off);
+        best = o < best ? o : best;
+    }
+    if ((threadIdx.x & 63) == 0) best_w[threadIdx.x >> 6] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < 4; ++w) best = best_w[w] < best ? best_w[w] : best;
+        evicted[bg] = (int32_t)~(uint32_t)best;         // (the host guarantees at least one competing token)
+    }
+}
+
+// Closes the gap the evicted token leaves: row j >= e takes row j + 1, for K, V (blockIdx.y = 0, 1; one 64-byte column
+// slice per workgroup, rows read chunk by chunk before they are overwritten, as in move_rows_in_place) and for the
+// running scores (blockIdx.y = 2), whose slots from len - 1 on are cleared.
+__global__ __launch_bounds__(kMoveThreads) void evict_shift(uint4 *__restrict__ k, uint4 *__restrict__ v,
+                                                            float *__restrict__ scores,
+                                                            const int32_t *__restrict__ evicted, int N, int Hkv,
+                                                            int ragged, SeqLens lens, int row_vec) {
+    const size_t bg = blockIdx.z;
+    const int len = seq_len_of(lens, ragged, (int)(bg / Hkv), N);
+    const int e = evicted[bg];
+    const int budget = len - 1;                      // rows that remain
+    if (e < 0 || e >= len) return;                   // (cannot happen: evict_pick chose among the live tokens)
+    if (blockIdx.y == 2) {
+        if (blockIdx.x != 0) return;
+        float *s = scores + bg * N;
+        for (int j0 = e; j0 < budget; j0 += kMoveThreads * kMoveRows) {
+            float x[kMoveRows];
+#pragma unroll
+            for (int u = 0; u < kMoveRows; ++u) {
+                const int j = j0 + u * kMoveThreads + threadIdx.x;
+                x[u] = j < budget ? s[j + 1] : 0.f;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kMoveRows; ++u) {
+                const int j = j0 + u * kMoveThreads + threadIdx.x;
+                if (j < budget) s[j] = x[u];
+            }
+        }
+        for (int j = budget + threadIdx.x; j < N; j += kMoveThreads) s[j] = 0.f;
+        return;
+    }
+    uint4 *rows = (blockIdx.y == 0 ? k : v) + bg * N * row_vec;
+    const int c = blockIdx.x * 4 + (threadIdx.x & 3);
+    const int r = threadIdx.x >> 2;
+    for (int j0 = e; j0 < budget; j0 += kMoveChunk) {
+        uint4 x[kMoveRows];
+#pragma unroll
+        for (int u = 0; u < kMoveRows; ++u) {
+            const int j = j0 + u * (kMoveThreads / 4) + r;
+            x[u] = make_uint4(0, 0, 0, 0);
+            if (j < budget && c < row_vec) x[u] = rows[(size_t)(j + 1) * row_vec + c];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int u = 0; u < kMoveRows; ++u) {
+            const int j = j0 + u * (kMoveThreads / 4) + r;
+            if (j < budget && c < row_vec) rows[(size_t)j * row_vec + c] = x[u];
+        }
+    }
+}
+
 // Measurement hook: reads `n_vec` 16-byte words once with 128-bit loads and folds them
 // into one word per thread (so the loads cannot be dropped).  Its duration gives the box's
 // own streaming-read ceiling, the practical denominator next to the nominal HBM peak.
@@ -165,6 +257,17 @@ hipError_t launch_compact_in_place(void *k, void *v, float *scores, const int32_
     const int row_vec = row_bytes / 16;
     const dim3 grid((unsigned)((row_vec + 3) / 4), scores ? 3 : 2, (unsigned)(B * Hkv));
     move_rows_in_place<<<grid, dim3(kMoveThreads), 0, stream>>>((uint4 *)k, (uint4 *)v, scores, keep_idx, N, budget, row_vec);
+    return hipGetLastError();
+}
+
+hipError_t launch_evict_one(void *k, void *v, float *scores, int32_t *evicted, int B, int Hkv, int N, int ragged,
+                            const SeqLens &lens, int first, int tail, int row_bytes, hipStream_t stream) {
+    evict_pick<<<dim3(B * Hkv), dim3(256), 0, stream>>>(scores, N, Hkv, ragged, lens, first, tail, evicted);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int row_vec = row_bytes / 16;
+    const dim3 grid((row_vec + 3) / 4, 3, B * Hkv);
+    evict_shift<<<grid, dim3(kMoveThreads), 0, stream>>>((uint4 *)k, (uint4 *)v, scores, evicted, N, Hkv, ragged, lens, row_vec);
     return hipGetLastError();
 }
 

@@ -97,6 +97,10 @@ hipError_t launch_compact(const void *k, const void *v, const int32_t *keep_idx,
                           int Hkv, int N, int budget, int row_bytes, hipStream_t stream);
 hipError_t launch_compact_in_place(void *k, void *v, float *scores, const int32_t *keep_idx, int B, int Hkv, int N,
                                    int budget, int row_bytes, hipStream_t stream);
+// Evict-one of a decoding step: picks, per (sequence, KV head), the lowest-scored token among first <= p < len - tail
+// (ties: the highest index) into `evicted`, then closes the gap in k, v and scores.
+hipError_t launch_evict_one(void *k, void *v, float *scores, int32_t *evicted, int B, int Hkv, int N, int ragged,
+                            const SeqLens &lens, int first, int tail, int row_bytes, hipStream_t stream);
 hipError_t launch_gather_scores(const float *in, const int32_t *keep_idx, float *out, int BH, int N, int budget,
                                  int n_out, hipStream_t stream);
 hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int blocks, hipStream_t stream);

@@ -331,6 +331,44 @@ int obc_compact_inplace(void *k, void *v, float *scores, const int32_t *keep_idx
     return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
 }
 
+int obc_decode_step_workspace_bytes(int B, int N, int Hq, int Hkv, int d, int dtype, int variant, size_t *bytes_out) {
+    if (!bytes_out) return OBC_EINVAL;
+    if (variant == OBC_ALL) return OBC_EINVAL;          // one running score per token
+    ScoreWorkspace ws;
+    const int rc = plan_score_workspace(B, N, 1, Hq, Hkv, d, dtype, variant, &ws);
+    if (rc != OBC_OK) return rc;
+    *bytes_out = ws.total + align_up((size_t)B * Hkv * sizeof(int32_t), 256);
+    return OBC_OK;
+}
+
+int obc_decode_step(const void *q, void *k, void *v, float *scores, int32_t *evicted, int N, int Hq, int Hkv, int d,
+                    int variant, int B, int dtype, const int32_t *seq_lens_host, int num_sinks, int num_recent,
+                    void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (variant == OBC_ALL || num_sinks < 0 || num_recent < 0) return OBC_EINVAL;
+    if (((uintptr_t)evicted & 3) != 0) return OBC_EINVAL;
+    size_t need = 0;
+    int rc = obc_decode_step_workspace_bytes(B, N, Hq, Hkv, d, dtype, variant, &need);
+    if (rc != OBC_OK) return rc;
+    // every sequence must hold a token that competes: num_sinks + num_recent < len_b (checked before anything runs)
+    int ragged = 0;
+    SeqLens lens;
+    std::memset(&lens, 0, sizeof(lens));
+    const long long protect = (long long)num_sinks + num_recent;
+    if (protect + 1 > N) return OBC_EINVAL;
+    rc = fill_lens(seq_lens_host, B, N, (int)protect + 1, &ragged, &lens);
+    if (rc != OBC_OK) return rc;
+    if (!workspace || ((uintptr_t)workspace & 255) != 0 || workspace_bytes < need) return OBC_EWORKSPACE;
+    const size_t score_bytes = need - align_up((size_t)B * Hkv * sizeof(int32_t), 256);
+    rc = score_impl(q, k, v, N, 1, Hq, Hkv, d, variant, scores, B, dtype, seq_lens_host, workspace, score_bytes, hip_stream,
+                    OBC_STAGE_ALL, 1);
+    if (rc != OBC_OK) return rc;
+    int32_t *pick = evicted ? evicted : (int32_t *)((char *)workspace + score_bytes);
+    const long long row_bytes = (long long)d * (dtype == OBC_F32 ? 4 : 2);
+    const hipError_t e = launch_evict_one(k, v, scores, pick, B, Hkv, N, ragged, lens, num_sinks, num_recent, (int)row_bytes,
+                                          (hipStream_t)hip_stream);
+    return e == hipSuccess ? OBC_OK : OBC_ELAUNCH;
+}
+
 int obc_compact_scores(const float *scores, const int32_t *keep_idx, float *scores_out, int B, int Hkv, int N,
                        int budget, int N_out, void *hip_stream) {
     if (!scores || !keep_idx || !scores_out) return OBC_EINVAL;

@@ -137,6 +137,22 @@ def test_entry_points_reject_bad_arguments_before_launch(lib):
     assert ip(fake, fake, None, fake, 1, 1, 16, 4, 6, 1, None) == obc.OBC_EUNSUPPORTED       # 12-byte rows
     assert ip(fake, fake, None, fake, 1, 1, 16, 4, 64, 7, None) == obc.OBC_EUNSUPPORTED      # dtype
 
+    ds = lib.obc_decode_step   # (q, k, v, scores, evicted, N, Hq, Hkv, d, variant, B, dtype, lens, sinks, recent, ws, ws_bytes, stream)
+    assert ds(fake, fake, fake, fake, fake, 1025, 32, 8, 128, obc.OBC_ALL, 1, 0, None, 4, 24, fake, 1 << 30, None) == obc.OBC_EINVAL
+    assert ds(fake, fake, fake, fake, fake, 1025, 32, 8, 128, 2, 1, 0, None, -1, 24, fake, 1 << 30, None) == obc.OBC_EINVAL
+    assert ds(fake, fake, fake, fake, fake, 28, 32, 8, 128, 2, 1, 0, None, 4, 24, fake, 1 << 30, None) == obc.OBC_EINVAL   # nothing competes
+    tiny = (ctypes.c_int32 * 1)(28)
+    assert ds(fake, fake, fake, fake, fake, 1025, 32, 8, 128, 2, 1, 0, tiny, 4, 24, fake, 1 << 30, None) == obc.OBC_EINVAL  # nor in this sequence
+    assert ds(fake, fake, fake, fake, ctypes.c_void_p(4098), 1025, 32, 8, 128, 2, 1, 0, None, 4, 24, fake, 1 << 30, None) == obc.OBC_EINVAL
+    assert ds(fake, fake, fake, fake, fake, 1025, 32, 8, 128, 2, 1, 0, None, 4, 24, None, 1 << 30, None) == obc.OBC_EWORKSPACE
+    assert ds(fake, fake, fake, fake, fake, 1025, 32, 8, 128, 2, 1, 0, None, 4, 24, fake, 256, None) == obc.OBC_EWORKSPACE
+    assert ds(None, fake, fake, fake, fake, 1025, 32, 8, 128, 2, 1, 0, None, 4, 24, fake, 1 << 30, None) == obc.OBC_EINVAL
+    assert ds(fake, fake, fake, None, fake, 1025, 32, 8, 128, 2, 1, 0, None, 4, 24, fake, 1 << 30, None) == obc.OBC_EINVAL
+    step = obc.obc_decode_step_workspace_bytes(1, 1025, 32, 8, 128, obc.OBC_BF16, obc.OBC_JOINT)
+    assert step == obc.obc_score_workspace_bytes(1, 1025, 1, 32, 8, 128, obc.OBC_BF16, obc.OBC_JOINT) + 256
+    with pytest.raises(obc.ObcError):
+        obc.obc_decode_step_workspace_bytes(1, 1025, 32, 8, 128, obc.OBC_BF16, obc.OBC_ALL)
+
 
 def test_plan_ignores_the_process_environment_and_follows_the_hooks(lib, monkeypatch):
     """The workspace plan is a function of the arguments and of obc_set_score_path / obc_set_score_tuning alone:

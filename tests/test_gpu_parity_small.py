@@ -214,7 +214,7 @@ def test_accumulate_onto_zeros_equals_plain_call_with_several_row_chunks():
     assert torch.equal(run, plain + plain)
 
 
-@pytest.mark.parametrize("in_place", [False, True])
+@pytest.mark.parametrize("in_place", [False, True, "one call"])
 def test_decode_eviction_loop_matches_oracle(in_place):
     """The decoding setup of Appendix C in miniature: every step appends a token, accumulates its scores, and once the
     cache is over budget evicts one token per head with sinks and a recent window protected.  The oracle runs the same
@@ -233,18 +233,35 @@ def test_decode_eviction_loop_matches_oracle(in_place):
     run = torch.zeros(B, Hkv, cap, dtype=torch.float32, device=dev)
     k_ref = np.zeros((B, Hkv, cap, d), np.float64); v_ref = np.zeros_like(k_ref)
     run_ref = np.zeros((B, Hkv, cap), np.float64)
+    one_call = in_place == "one call"
+    if one_call:
+        kf, vf, runf = k.clone(), v.clone(), run.clone()
     length, evictions = 0, 0
     for t in range(T):
         k[:, :, length] = ks[t].to(dev); v[:, :, length] = vs[t].to(dev)
         k_ref[:, :, length] = ks[t].double().numpy(); v_ref[:, :, length] = vs[t].double().numpy()
         length += 1
         lens = [length] * B
+        if one_call:
+            # The same step through obc_decode_step on a cache of its own: one call accumulates, drops one token per
+            # head and closes the gap.  The three-call path below is held to the oracle; the one call must agree with it
+            # bit for bit, and report the position it dropped.
+            kf[:, :, length - 1] = ks[t].to(dev); vf[:, :, length - 1] = vs[t].to(dev)
+            if length > budget:
+                evicted = obc.obc_decode_step(qs[t].to(dev), kf, vf, runf, "joint", sinks, recent, seq_lens=lens).cpu().numpy()
+            else:
+                obc.obc_score(qs[t].to(dev), kf, vf, "joint", seq_lens=lens, scores=runf, accumulate=True)
         obc.obc_score(qs[t].to(dev), k, v, "joint", seq_lens=lens, scores=run, accumulate=True)
         run_ref += np.asarray(oracle.score(qs[t].double().numpy(), k_ref, v_ref, seq_lens=lens))[2]
         if length > budget:
             keep = obc.obc_select_protected(run, hh, sinks, recent, 0, seq_lens=lens)
             keep_np = keep.cpu().numpy()
             np.testing.assert_array_equal(keep_np, oracle.select_protected(run.cpu().numpy(), hh, sinks, recent, 0, lens))
+            if one_call:
+                for b in range(B):
+                    for h in range(Hkv):
+                        gone = np.setdiff1d(np.arange(length), keep_np[b, h])
+                        assert gone.tolist() == [int(evicted[b, h])], (t, b, h, gone, evicted[b, h])
             if in_place:
                 obc.obc_compact_inplace(k, v, keep, scores=run)
                 k[:, :, budget:] = 0; v[:, :, budget:] = 0        # stale rows; cleared only to compare whole caches below
@@ -264,6 +281,9 @@ def test_decode_eviction_loop_matches_oracle(in_place):
             evictions += 1
             np.testing.assert_array_equal(k.double().cpu().numpy(), k_ref)         # the caches stay identical
             assert np.all(run.cpu().numpy()[:, :, budget:] == 0.0)
+            if one_call:
+                assert torch.equal(kf[:, :, :budget], k[:, :, :budget]) and torch.equal(vf[:, :, :budget], v[:, :, :budget])
+                assert torch.equal(runf, run), "step %d" % t
         if t % 10 == 9 or t == T - 1:
             err, where = score_error(run.cpu().numpy(), run_ref, min(hh, length), [length] * B, TOL["bf16"])
             assert err <= TOL["bf16"], "step %d: err %.3g at %s" % (t, err, where)
@@ -434,3 +454,42 @@ def test_compact_inplace_matches_oracle_gather(dtype, d, N):
     np.testing.assert_array_equal(bits(vd).cpu().numpy()[:, :, :40], vref)
     assert np.all(sd.cpu().numpy()[:, :, 25:] == 0.0)
     np.testing.assert_array_equal(sd.cpu().numpy()[:, :, :25], s.numpy()[:, :, 5:30])
+
+
+@pytest.mark.parametrize("variant", ["key", "value", "joint"])
+def test_decode_step_on_a_ragged_batch_with_ties(variant):
+    """obc_decode_step on sequences of different lengths, one of them with every candidate tied (zero query, equal
+    value rows: Eq. 4-6 then give every token the same score): the accumulated scores equal obc_score's own, the
+    dropped position is the oracle's choice on those fp32 scores (lowest score, the later position among equals, sinks
+    and the recent window exempt), and K, V and scores close the gap exactly."""
+    B, Hq, Hkv, d, N = 3, 8, 2, 128, 200
+    sinks, recent = 4, 16
+    lens = [200, 77, 131]
+    g = torch.Generator().manual_seed(97)
+    q = torch.randn(B, Hq, 1, d, generator=g).to(torch.bfloat16)
+    k = torch.randn(B, Hkv, N, d, generator=g).to(torch.bfloat16)
+    v = torch.randn(B, Hkv, N, d, generator=g).to(torch.bfloat16)
+    run = torch.rand(B, Hkv, N, generator=g) * 0.01
+    q[1] = 0; v[1] = v[1, :, :1]; run[1] = 0.25                       # sequence 1: all tied
+    for b, L in enumerate(lens):
+        run[b, :, L:] = 0
+    dev = torch.device("cuda")
+    q, k, v, run = q.to(dev), k.to(dev), v.to(dev), run.to(dev)
+    acc = run.clone()
+    obc.obc_score(q, k, v, variant, seq_lens=lens, scores=acc, accumulate=True)
+    k0, v0 = k.clone(), v.clone()
+    evicted = obc.obc_decode_step(q, k, v, run, variant, sinks, recent, seq_lens=lens).cpu().numpy()
+    acc_np = acc.cpu().numpy()
+    for b, L in enumerate(lens):
+        keep = oracle.select_protected(acc_np[b:b + 1], L - sinks - recent - 1, sinks, recent, 0, [L])[0]     # [Hkv, L-1]
+        for h in range(Hkv):
+            gone = np.setdiff1d(np.arange(L), keep[h])
+            assert gone.tolist() == [int(evicted[b, h])], (b, h, gone, evicted[b, h])
+            if b == 1:
+                assert evicted[b, h] == L - recent - 1
+            idx = torch.from_numpy(keep[h]).long().to(dev)
+            assert torch.equal(k[b, h, :L - 1], k0[b, h].index_select(0, idx))
+            assert torch.equal(v[b, h, :L - 1], v0[b, h].index_select(0, idx))
+            assert torch.equal(run[b, h, :L - 1], acc[b, h].index_select(0, idx))
+            assert (run[b, h, L - 1:] == 0).all()
+            assert torch.equal(k[b, h, L:], k0[b, h, L:])             # rows past the sequence are left alone
