@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--workload", default="c3")
     ap.add_argument("--variant", default="joint")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--plain", action="store_true",
+                    help="skip the side measurements (two streams, sink-dominated inputs): for runs under a profiler, whose "
+                         "per-kernel durations they would blur")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = the whole batch)")
     ap.add_argument("--decode", action="store_true",
                     help="time one decoding step per layer instead (W=1 accumulate, evict one token, compact); "
@@ -78,9 +81,16 @@ def decode_step_bench(args, torch, obc):
         obc.obc_select_protected(run, hh, sinks, recent, 0, keep_idx=keep)
         obc.obc_compact_inplace(k, v, keep, scores=run)
 
+    ws_step = torch.empty(obc.obc_decode_step_workspace_bytes(B, N, Hq, Hkv, d, obc.OBC_BF16, var), dtype=torch.uint8, device=dev)
+    evicted = torch.empty(B, Hkv, dtype=torch.int32, device=dev)
+
+    def step_one_call(i):
+        obc.obc_decode_step(q, k, v, run, var, sinks, recent, evicted=evicted, workspace=ws_step)
+
     for i in range(args.warmup):
         step_gather(i)
         step_inplace(i)
+        step_one_call(i)
     torch.cuda.synchronize()
     it = max(args.steps, 50)
     out = {"metric": "decode step latency per layer (W=1 accumulate + evict one + compact)", "unit": "us", "n_gpus": 1,
@@ -89,8 +99,9 @@ def decode_step_bench(args, torch, obc):
                       "sinks": sinks, "recent": recent, "variant": args.variant},
            "score_accumulate_us": round(timed(score, it, torch) * 1e3, 2),
            "step_gather_us": round(timed(step_gather, it, torch) * 1e3, 2),
-           "step_inplace_us": round(timed(step_inplace, it, torch) * 1e3, 2)}
-    out["value"] = out["step_inplace_us"]
+           "step_inplace_us": round(timed(step_inplace, it, torch) * 1e3, 2),
+           "step_one_call_us": round(timed(step_one_call, it, torch) * 1e3, 2)}
+    out["value"] = out["step_one_call_us"]
     print(json.dumps(out))
 
 
@@ -103,6 +114,36 @@ def timed(fn, iters, torch):
     e1.record()
     e1.synchronize()
     return e0.elapsed_time(e1) / iters
+
+
+def parity_diagnostics(torch, np, oracle, ref, keep_ref, vi, nb, sub_lens, wl, N, Hkv, nvar, scores, keep, score, select):
+    """GPU scores of input set 0 against the oracle's on the sampled sequences, and the GPU's kept indices against the
+    oracle's selection on the oracle's own scores (outside every timed region)."""
+    if keep_ref is None:
+        keep_ref = oracle.select(ref.astype("float32"), wl.budget, sub_lens)
+    score(0)
+    select(0)
+    torch.cuda.synchronize()
+    g_scores = (scores[vi] if nvar == 3 else scores)[:nb].cpu().numpy()
+    g_keep = keep[:nb].cpu().numpy()
+    tol = 1e-3 if wl.dtype == "bf16" else 1e-5
+    rel, in_band, out_band = [], 0, 0
+    for b in range(nb):
+        L = sub_lens[b] if sub_lens else N
+        for h in range(Hkv):
+            r, g = ref[b, h, :L], g_scores[b, h, :L]
+            nz = r != 0
+            rel.append(np.abs(g - r)[nz] / np.abs(r[nz]))
+            tau = np.partition(r, L - wl.budget)[L - wl.budget]
+            differ = np.setxor1d(g_keep[b, h], keep_ref[b, h])
+            band = np.abs(r[differ] - tau) <= 2 * tol * tau
+            in_band += int(band.sum())
+            out_band += int((~band).sum())
+    rel = np.concatenate(rel)
+    return {"max_rel_err": float(rel.max()), "p999_rel_err": float(np.quantile(rel, 0.999)),
+            "idx_mismatch_in_band": in_band, "idx_mismatch_out_of_band": out_band,
+            "note": "GPU vs the fp64 oracle on the cpu_baseline sample, no floor; band = +-2 tol around each head's "
+                    "budget-th largest oracle score (tokens inside it may legitimately swap)"}
 
 
 def main():
@@ -178,7 +219,7 @@ def main():
     # Side measurement: the same K steps with consecutive steps (independent inputs, outputs and workspaces) on two
     # streams, so that the narrow select and gather kernels of one step overlap the next step's sweeps.
     pipe = []
-    for i in range(2):
+    for i in range(0 if args.plain else 2):
         pipe.append({"stream": torch.cuda.Stream(), "ws": torch.empty_like(ws), "scores": torch.empty_like(scores),
                      "keep": torch.empty_like(keep), "k_out": torch.empty_like(k_out), "v_out": torch.empty_like(v_out)})
 
@@ -189,14 +230,16 @@ def main():
             obc.obc_select(p["scores"][2] if nvar == 3 else p["scores"], wl.budget, seq_lens=lens, keep_idx=p["keep"])
             obc.obc_compact(s["k"], s["v"], p["keep"], k_out=p["k_out"], v_out=p["v_out"])
 
-    for i in range(min(args.warmup, 50)):
-        step_on(i)
-    torch.cuda.synchronize()
-    p0 = time.perf_counter()
-    for i in range(args.steps):
-        step_on(i)
-    torch.cuda.synchronize()
-    ms_pipelined = (time.perf_counter() - p0) * 1e3 / args.steps
+    ms_pipelined = None
+    if not args.plain:
+        for i in range(min(args.warmup, 50)):
+            step_on(i)
+        torch.cuda.synchronize()
+        p0 = time.perf_counter()
+        for i in range(args.steps):
+            step_on(i)
+        torch.cuda.synchronize()
+        ms_pipelined = (time.perf_counter() - p0) * 1e3 / args.steps
     del pipe
 
     # Per-stage device durations (events on the launch stream), same alternating inputs.
@@ -221,35 +264,48 @@ def main():
     ms_stream = timed(stream, it, torch)
     # The same call on inputs where ONE key (an attention sink) holds nearly all of every window row's attention:
     # its cost must not depend on that (side measurement; the metric above is on the workload's own inputs).
-    import dataclasses
-    sink_wl = dataclasses.replace(wl, shared_query=1.0, sink_gain=3.0, sinks=1)
-    sx = synth.make_inputs(sink_wl, layer=0)
-    sset = {k: (v.to(dev) if torch.is_tensor(v) else v) for k, v in sx.items()}
+    ms_sink = None
+    if not args.plain:
+        import dataclasses
+        sink_wl = dataclasses.replace(wl, shared_query=1.0, sink_gain=3.0, sinks=1)
+        sx = synth.make_inputs(sink_wl, layer=0)
+        sset = {k: (v.to(dev) if torch.is_tensor(v) else v) for k, v in sx.items()}
 
-    def score_sink(i):
-        obc.obc_score(sset["q"], sset["k"], sset["v"], var, seq_lens=lens, scores=scores, workspace=ws)
+        def score_sink(i):
+            obc.obc_score(sset["q"], sset["k"], sset["v"], var, seq_lens=lens, scores=scores, workspace=ws)
 
-    score_sink(0)
-    ms_sink = timed(score_sink, it, torch)
-    del sset, sx
+        score_sink(0)
+        ms_sink = timed(score_sink, it, torch)
+        del sset, sx
     esize = 2 if wl.dtype == "bf16" else 4
     head_tokens = tokens * Hkv
     algo_bytes = head_tokens * 2 * d * esize + B * Hq * W * d * esize + nvar * B * Hkv * N * 4
     achieved = algo_bytes / (ms["obc_score"] * 1e-3) / 1e9
     mfma_flops = 4 * 2 * Hq * W * d * tokens
-    traffic = None
-    # measured HBM bytes of one obc_score call, from the committed counter summary of this workload
+    traffic, traffic_source = None, None
+    # HBM bytes of one obc_score call as rocprofv3's counters measured them in a separate profiling run: read from the
+    # committed counter summary of this workload (not measured by this run; the file says how it was made)
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % wl.name)
     if os.path.exists(tpath):
         import re
         with open(tpath) as f:
             m = re.search(r"obc_score \(all mfma_\* kernels\):.*?=\s*(\d+) bytes per call", f.read())
         traffic = int(m.group(1)) if m else None
+        traffic_source = "profiles/" + os.path.basename(tpath) if m else None
+    # Vector-ALU load of the two sweeps beside the memory roofline: per (window row, token) pair the kernels issue ~21
+    # fp32 lane-operations (exp2 counted as 4: quarter rate) and the matrix ops take the vector issue port for another
+    # ~9 lane-operations' worth; the chip issues 256 CUs x 4 SIMDs x 16 lanes per clock at 2.4 GHz (no packed fp32).
+    pairs = Hq * W * tokens
+    valu_rate = 256 * 4 * 16 * 2.4e9
+    valu_ms = pairs * (21 + 9) / valu_rate * 1e3
     roofline = {
         "bound": "hbm", "kernel": "obc_score = mfma_sweep1 + mfma_combine + mfma_sweep2",
         "achieved": round(achieved, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-        "frac": round(achieved / PEAK_HBM_GBPS, 4), "traffic": traffic,
+        "frac": round(achieved / PEAK_HBM_GBPS, 4), "traffic": traffic, "traffic_source": traffic_source,
         "algorithmic_bytes": algo_bytes,
+        "valu": {"pairs": pairs, "lane_ops_per_pair": 21, "mfma_issue_lane_ops_per_pair": 9,
+                 "peak_lane_ops_per_s": valu_rate, "ms_at_peak": round(valu_ms, 4),
+                 "frac": round(valu_ms / ms["obc_score"], 4)},
         "kernel_ms": {k: round(v, 4) for k, v in ms.items()},
         # plain streaming read of the same K and V buffers on this machine: the practical ceiling
         "stream_read_GBps": round(2 * sets[0]["k"].numel() * esize / (ms_stream * 1e-3) / 1e9, 1),
@@ -258,9 +314,10 @@ def main():
                  "peak_TFLOPs": 2500.0, "frac": round(mfma_flops / (ms["obc_score"] * 1e-3) / 2.5e15, 4)},
     }
 
-    cpu = None
+    cpu, parity = None, None
     if not args.no_cpu_baseline:
         import oracle
+        import numpy as np
         x = synth.make_inputs(wl, layer=0)
         nb = B if args.cpu_seqs <= 0 else min(args.cpu_seqs, B)
         sub_lens = lens[:nb] if lens else None
@@ -279,6 +336,11 @@ def main():
                       "compact, %.1f s wall on %d threads" % (nb, B, Hkv, cpu_tokens * Hkv, c1 - c0,
                                                              oracle.num_threads()),
         }
+        # Parity diagnostics on the same sample, outside every timed region.
+        vi = {"value": 0, "key": 1, "joint": 2, "all": 2}.get(args.variant)
+        if vi is not None:
+            parity = parity_diagnostics(torch, np, oracle, s[vi], keep_ref if vi == 2 else None, vi, nb, sub_lens, wl,
+                                        N, Hkv, nvar, scores, keep, score, select)
         del keep_ref
 
     out = {
@@ -292,10 +354,11 @@ def main():
                     "max": round(per_step[-1], 4)},
         "head_tokens_per_s": round(head_tokens / (ms_per_step * 1e-3), 1),
         "score_only_tokens_per_s": round(tokens / (ms["obc_score"] * 1e-3), 1),
-        "obc_score_ms_one_sink_dominates_every_row": round(ms_sink, 4),
-        "two_streams": {"ms_per_step": round(ms_pipelined, 4), "tokens_per_s": round(tokens / (ms_pipelined * 1e-3), 1),
-                        "note": "consecutive steps alternate between two streams; not the headline value"},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "obc_score_ms_one_sink_dominates_every_row": None if ms_sink is None else round(ms_sink, 4),
+        "two_streams": None if ms_pipelined is None else {
+            "ms_per_step": round(ms_pipelined, 4), "tokens_per_s": round(tokens / (ms_pipelined * 1e-3), 1),
+            "note": "consecutive steps alternate between two streams; not the headline value"},
+        "roofline": roofline, "cpu_baseline": cpu, "parity": parity,
     }
     print(json.dumps(out))
 
