@@ -7,9 +7,13 @@ workload is the one the headline metric is quoted on: c3, one LLaMA-3.1-8B-shape
 (32 query / 8 KV heads, d=128, W=32, bf16), batch 4, N=32768, budget 2048.
 
 Prints ONE JSON line: whole-path throughput in scored KV tokens/s, the HBM roofline of the
-scoring call (algorithmic bytes: K and V once, Q, scores) from durations measured here with
-events on the launch stream, per-kernel durations, and the fp64 CPU oracle timed on a
+scoring call (algorithmic bytes: K and V once, Q, scores) from its duration inside the timed
+region (events on the launch stream), per-kernel durations, and the fp64 CPU oracle timed on a
 bounded sample of the same workload (a reported baseline, not a target).
+
+Order of a run: the oracle on the CPU; the side measurements (per-stage loops, streaming-read
+probe, sink-dominated inputs, two streams); W untimed steps; exactly K timed steps between two
+synchronisations; parity diagnostics against the oracle's sample.
 """
 from __future__ import annotations
 
@@ -38,6 +42,8 @@ def parse():
     ap.add_argument("--plain", action="store_true",
                     help="skip the side measurements (two streams, sink-dominated inputs): for runs under a profiler, whose "
                          "per-kernel durations they would blur")
+    ap.add_argument("--timed-first", action="store_true",
+                    help="run the timed region before the side measurements instead of after them")
     ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences the oracle is timed on (0 = the whole batch)")
     ap.add_argument("--decode", action="store_true",
                     help="time one decoding step per layer instead (W=1 accumulate, evict one token, compact); "
@@ -201,71 +207,65 @@ def main():
         select(i)
         compact(i)
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
-    t0 = time.perf_counter()
-    marks[0].record()
-    for i in range(args.steps):
-        step(i)
-        marks[i + 1].record()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    value = tokens / (ms_per_step * 1e-3)
-    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))   # device time of each step
+    # The fp64 oracle on the CPU first (seconds of host work during which the GPU idles), so that nothing sits between
+    # the GPU-side measurements below and the timed region.
+    cpu, oracle_out = None, None
+    if not args.no_cpu_baseline:
+        import oracle
+        import numpy as np
+        x = synth.make_inputs(wl, layer=0)
+        nb = B if args.cpu_seqs <= 0 else min(args.cpu_seqs, B)
+        sub_lens = lens[:nb] if lens else None
+        c0 = time.perf_counter()
+        s_ref = oracle.score(x["q"][:nb], x["k"][:nb], x["v"][:nb], seq_lens=sub_lens)
+        keep_ref = oracle.select(s_ref[2].astype("float32"), wl.budget, sub_lens)
+        kb, vb = (x[t][:nb].view(torch.int16).numpy() for t in ("k", "v")) if wl.dtype == "bf16" else \
+                 (x[t][:nb].numpy() for t in ("k", "v"))
+        oracle.compact(kb, vb, keep_ref)
+        c1 = time.perf_counter()
+        cpu_tokens = sum(sub_lens) if sub_lens else nb * N
+        cpu = {
+            "value": round(cpu_tokens / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.num_threads(),
+            "kind": "oracle",
+            "sample": "%d of %d sequences, all %d KV heads (%d head-tokens): fp64 score (3 variants) + select + "
+                      "compact, %.1f s wall on %d threads" % (nb, B, Hkv, cpu_tokens * Hkv, c1 - c0,
+                                                             oracle.num_threads()),
+        }
+        oracle_out = (s_ref, keep_ref, nb, sub_lens)
+        del x, kb, vb
 
-    # Side measurement: the same K steps with consecutive steps (independent inputs, outputs and workspaces) on two
-    # streams, so that the narrow select and gather kernels of one step overlap the next step's sweeps.
-    pipe = []
-    for i in range(0 if args.plain else 2):
-        pipe.append({"stream": torch.cuda.Stream(), "ws": torch.empty_like(ws), "scores": torch.empty_like(scores),
-                     "keep": torch.empty_like(keep), "k_out": torch.empty_like(k_out), "v_out": torch.empty_like(v_out)})
-
-    def step_on(i):
-        s, p = sets[i & 1], pipe[i & 1]
-        with torch.cuda.stream(p["stream"]):
-            obc.obc_score(s["q"], s["k"], s["v"], var, seq_lens=lens, scores=p["scores"], workspace=p["ws"])
-            obc.obc_select(p["scores"][2] if nvar == 3 else p["scores"], wl.budget, seq_lens=lens, keep_idx=p["keep"])
-            obc.obc_compact(s["k"], s["v"], p["keep"], k_out=p["k_out"], v_out=p["v_out"])
-
-    ms_pipelined = None
-    if not args.plain:
-        for i in range(min(args.warmup, 50)):
-            step_on(i)
-        torch.cuda.synchronize()
-        p0 = time.perf_counter()
-        for i in range(args.steps):
-            step_on(i)
-        torch.cuda.synchronize()
-        ms_pipelined = (time.perf_counter() - p0) * 1e3 / args.steps
-    del pipe
-
-    # Per-stage device durations (events on the launch stream), same alternating inputs.
     it = min(max(args.steps, 10), 100)
-    ms = {
-        "obc_score": timed(score, it, torch),
-        "sweep1": timed(lambda i: score(i, obc.OBC_STAGE_SWEEP1), it, torch),
-        "combine": timed(lambda i: score(i, obc.OBC_STAGE_COMBINE), it, torch),
-        "sweep2": timed(lambda i: score(i, obc.OBC_STAGE_SWEEP2), it, torch),
-        "obc_select": timed(select, it, torch),
-        "obc_compact": timed(compact, it, torch),
-    }
-    # The box's own streaming-read rate over the same K and V buffers (plain 128-bit loads).
-    sink = torch.empty(obc.OBC_PROBE_BLOCKS * 256, dtype=torch.int32, device=dev)
+    side = {}
 
-    def stream(i):
-        s = sets[i & 1]
-        obc.obc_probe_read_bandwidth(s["k"], sink)
-        obc.obc_probe_read_bandwidth(s["v"], sink)
+    def side_measurements():
+        """Per-stage durations, the box's streaming-read rate, the sink-dominated inputs and the two-stream variant:
+        diagnostics beside the headline number, each on its own loop of launches."""
+        # Per-stage device durations (events on the launch stream), same alternating inputs; a hundred untimed steps
+        # first, so that the stage loops are not the ones that see the clocks ramp up after idle.
+        for i in range(100):
+            step(i)
+        side["stages"] = {
+            "sweep1": timed(lambda i: score(i, obc.OBC_STAGE_SWEEP1), it, torch),
+            "combine": timed(lambda i: score(i, obc.OBC_STAGE_COMBINE), it, torch),
+            "sweep2": timed(lambda i: score(i, obc.OBC_STAGE_SWEEP2), it, torch),
+            "obc_select": timed(select, it, torch),
+            "obc_compact": timed(compact, it, torch),
+        }
+        # The box's own streaming-read rate over the same K and V buffers (plain 128-bit loads).
+        sink = torch.empty(obc.OBC_PROBE_BLOCKS * 256, dtype=torch.int32, device=dev)
 
-    stream(0)
-    ms_stream = timed(stream, it, torch)
-    # The same call on inputs where ONE key (an attention sink) holds nearly all of every window row's attention:
-    # its cost must not depend on that (side measurement; the metric above is on the workload's own inputs).
-    ms_sink = None
-    if not args.plain:
+        def stream(i):
+            s = sets[i & 1]
+            obc.obc_probe_read_bandwidth(s["k"], sink)
+            obc.obc_probe_read_bandwidth(s["v"], sink)
+
+        stream(0)
+        side["ms_stream"] = timed(stream, it, torch)
+        side["ms_sink"], side["ms_pipelined"] = None, None
+        if args.plain:
+            return
+        # The same call on inputs where ONE key (an attention sink) holds nearly all of every window row's attention:
+        # its cost must not depend on that (side measurement; the metric is on the workload's own inputs).
         import dataclasses
         sink_wl = dataclasses.replace(wl, shared_query=1.0, sink_gain=3.0, sinks=1)
         sx = synth.make_inputs(sink_wl, layer=0)
@@ -275,8 +275,65 @@ def main():
             obc.obc_score(sset["q"], sset["k"], sset["v"], var, seq_lens=lens, scores=scores, workspace=ws)
 
         score_sink(0)
-        ms_sink = timed(score_sink, it, torch)
+        side["ms_sink"] = timed(score_sink, it, torch)
         del sset, sx
+        # The same K steps with consecutive steps (independent inputs, outputs and workspaces) on two streams, so that
+        # the narrow select and gather kernels of one step overlap the next step's sweeps.
+        pipe = []
+        for i in range(2):
+            pipe.append({"stream": torch.cuda.Stream(), "ws": torch.empty_like(ws), "scores": torch.empty_like(scores),
+                         "keep": torch.empty_like(keep), "k_out": torch.empty_like(k_out), "v_out": torch.empty_like(v_out)})
+
+        def step_on(i):
+            s, p = sets[i & 1], pipe[i & 1]
+            with torch.cuda.stream(p["stream"]):
+                obc.obc_score(s["q"], s["k"], s["v"], var, seq_lens=lens, scores=p["scores"], workspace=p["ws"])
+                obc.obc_select(p["scores"][2] if nvar == 3 else p["scores"], wl.budget, seq_lens=lens, keep_idx=p["keep"])
+                obc.obc_compact(s["k"], s["v"], p["keep"], k_out=p["k_out"], v_out=p["v_out"])
+
+        for i in range(min(args.warmup, 50)):
+            step_on(i)
+        torch.cuda.synchronize()
+        p0 = time.perf_counter()
+        for i in range(args.steps):
+            step_on(i)
+        torch.cuda.synchronize()
+        side["ms_pipelined"] = (time.perf_counter() - p0) * 1e3 / args.steps
+
+    step(0)
+    torch.cuda.synchronize()
+    # The side measurements run BEFORE the timed region by default: they are a few hundred launches, after which the
+    # chip's clock management has settled, so the timed region measures sustained throughput also when it is short
+    # (--timed-first restores the other order: then a short run right after idle reads some 20 % slower).
+    if not args.timed_first:
+        side_measurements()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    scored = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    marks[0].record()
+    for i in range(args.steps):
+        score(i)
+        scored[i].record()
+        select(i)
+        compact(i)
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = tokens / (ms_per_step * 1e-3)
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))   # device time of each step
+    # obc_score's launch-to-completion time inside the timed region itself (events on the launch stream)
+    ms_score_timed = sum(marks[i].elapsed_time(scored[i]) for i in range(args.steps)) / args.steps
+
+    if args.timed_first:
+        side_measurements()
+    ms = {"obc_score": ms_score_timed}
+    ms.update(side["stages"])
+    ms_stream, ms_sink, ms_pipelined = side["ms_stream"], side["ms_sink"], side["ms_pipelined"]
     esize = 2 if wl.dtype == "bf16" else 4
     head_tokens = tokens * Hkv
     algo_bytes = head_tokens * 2 * d * esize + B * Hq * W * d * esize + nvar * B * Hkv * N * 4
@@ -314,34 +371,16 @@ def main():
                  "peak_TFLOPs": 2500.0, "frac": round(mfma_flops / (ms["obc_score"] * 1e-3) / 2.5e15, 4)},
     }
 
-    cpu, parity = None, None
-    if not args.no_cpu_baseline:
-        import oracle
+    parity = None
+    if oracle_out is not None:
+        # Parity diagnostics on the oracle's sample, outside every timed region.
         import numpy as np
-        x = synth.make_inputs(wl, layer=0)
-        nb = B if args.cpu_seqs <= 0 else min(args.cpu_seqs, B)
-        sub_lens = lens[:nb] if lens else None
-        c0 = time.perf_counter()
-        s = oracle.score(x["q"][:nb], x["k"][:nb], x["v"][:nb], seq_lens=sub_lens)
-        keep_ref = oracle.select(s[2].astype("float32"), wl.budget, sub_lens)
-        kb, vb = (x[t][:nb].view(torch.int16).numpy() for t in ("k", "v")) if wl.dtype == "bf16" else \
-                 (x[t][:nb].numpy() for t in ("k", "v"))
-        oracle.compact(kb, vb, keep_ref)
-        c1 = time.perf_counter()
-        cpu_tokens = sum(sub_lens) if sub_lens else nb * N
-        cpu = {
-            "value": round(cpu_tokens / (c1 - c0), 1), "unit": "tokens/s", "cores": oracle.num_threads(),
-            "kind": "oracle",
-            "sample": "%d of %d sequences, all %d KV heads (%d head-tokens): fp64 score (3 variants) + select + "
-                      "compact, %.1f s wall on %d threads" % (nb, B, Hkv, cpu_tokens * Hkv, c1 - c0,
-                                                             oracle.num_threads()),
-        }
-        # Parity diagnostics on the same sample, outside every timed region.
+        import oracle
+        s_ref, keep_ref, nb, sub_lens = oracle_out
         vi = {"value": 0, "key": 1, "joint": 2, "all": 2}.get(args.variant)
         if vi is not None:
-            parity = parity_diagnostics(torch, np, oracle, s[vi], keep_ref if vi == 2 else None, vi, nb, sub_lens, wl,
+            parity = parity_diagnostics(torch, np, oracle, s_ref[vi], keep_ref if vi == 2 else None, vi, nb, sub_lens, wl,
                                         N, Hkv, nvar, scores, keep, score, select)
-        del keep_ref
 
     out = {
         "metric": "scored KV tokens/sec (all heads) at N=32K; achieved HBM GB/s vs peak",

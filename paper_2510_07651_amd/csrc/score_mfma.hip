@@ -147,10 +147,20 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
     if (!wave_active) return;
 
     // ---- matrix cores: block n+1 ----
+    // (with kNeedO the operand reads of the whole chain are issued up front, so that one LDS latency is exposed
+    // instead of one per pair of matrix ops, and the first value operands follow them ahead of the vote below)
     f32x16 s_next = zero16();
+    bf16x8 ka[8], va0[4];
+    if (kNeedO) {
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) ka[kk] = lds_read16(smem + kKBase + koff[kk]);
+#pragma unroll
+        for (int ddb = 0; ddb < 4; ++ddb) va0[ddb] = lds_read_vt(smem + kVBase + voff[ddb]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-        const bf16x8 a = lds_read16(smem + kKBase + koff[kk]);
+        const bf16x8 a = kNeedO ? ka[kk] : lds_read16(smem + kKBase + koff[kk]);
         s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.q[kk], s_next, 0, 0, 0);
     }
     // ---- vector ALUs: block n ----
@@ -219,10 +229,10 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
         }
         // ---- matrix cores: block n-1 ----
 #pragma unroll
-        for (int ddb = 0; ddb < 4; ++ddb)
+        for (int sx = 0; sx < 2; ++sx)
 #pragma unroll
-            for (int sx = 0; sx < 2; ++sx) {
-                const bf16x8 a = lds_read_vt(smem + kVBase + 16 * sx * kRowBytes + voff[ddb]);
+            for (int ddb = 0; ddb < 4; ++ddb) {
+                const bf16x8 a = sx == 0 ? va0[ddb] : lds_read_vt(smem + kVBase + 16 * kRowBytes + voff[ddb]);
                 R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.phi[sx].v, R.oacc[ddb], 0, 0, 0);
                 R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.plo[sx].v, R.oacc[ddb], 0, 0, 0);
             }
@@ -401,8 +411,7 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
         }
     }
     wait_async_loads();        // the blocks fetched past the end must have landed before the LDS is given back
-    if (!wave_active) return;
-    if (kNeedO) {      // drain: P V of the last block (n_total - 1, in slot 3 of the V ring)
+    if (kNeedO && wave_active) {      // drain: P V of the last block (n_total - 1, in slot 3 of the V ring)
         if (R.rescale) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -417,9 +426,6 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
                 R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.phi[sx].v, R.oacc[ddb], 0, 0, 0);
                 R.oacc[ddb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.plo[sx].v, R.oacc[ddb], 0, 0, 0);
             }
-    }
-
-    if (kNeedO) {
         if (first_ev.x >= 0) add_back_apply(R, first_row, __int_as_float(first_ev.y), R.m_ref, R.m_ref, half);
         for (int e = 1; e < kEvents; ++e) {
             if (!__any(e < R.n_ev)) break;       // uniform
@@ -429,24 +435,35 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
             }
         }
     }
+    if (kNeedO) __syncthreads();      // every wave is done with the rings: their space now stages the output rows
+    if (!wave_active) return;
     const float lrow = halves_sum(R.lsum);
-    const size_t prow = ((size_t)bg * n_splits + split) * m_pad + row;
-    if (half == 0) {
-        part_ml[prow * 4 + 0] = R.m_ref;         // raw q.k units; -inf when the split holds no visible key
-        part_ml[prow * 4 + 1] = lrow;
-        part_ml[prow * 4 + 2] = kNeedO ? R.cand_val : R.m_true;
-        part_ml[prow * 4 + 3] = __int_as_float(kNeedO ? R.cand_tok : 0);
-    }
+    const size_t prow0 = ((size_t)bg * n_splits + split) * m_pad + rb * 32;     // the wave's first row
+    if (half == 0)                    // reference in raw q.k units (-inf when the split holds no visible key), sum, candidate
+        *(float4 *)(part_ml + (prow0 + (lane & 31)) * 4) =
+            make_float4(R.m_ref, lrow, kNeedO ? R.cand_val : R.m_true, __int_as_float(kNeedO ? R.cand_tok : 0));
     if (kNeedO) {
-        float *dst = part_o + prow * kD;
+        // A lane holds 64 scattered entries of its row: written straight out, every store would touch 64 rows' worth of
+        // cache lines 16 bytes at a time.  The wave's 32 rows pass through its own 16 KB of LDS instead (16-byte slot c
+        // of row r at slot c ^ r: conflict-free both ways) and leave as whole rows, 1 KB per store.
+        char *stage = smem + wave * (32 * kD * 4);
+        const int r = lane & 31;
 #pragma unroll
         for (int ddb = 0; ddb < 4; ++ddb)
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
-                const int dd = ddb * 32 + 8 * r4 + 4 * half;
-                *(float4 *)(dst + dd) = make_float4(R.oacc[ddb][4 * r4], R.oacc[ddb][4 * r4 + 1],
-                                                    R.oacc[ddb][4 * r4 + 2], R.oacc[ddb][4 * r4 + 3]);
+                const int c = ddb * 8 + 2 * r4 + half;
+                *(float4 *)(stage + r * (kD * 4) + ((c ^ r) << 4)) =
+                    make_float4(R.oacc[ddb][4 * r4], R.oacc[ddb][4 * r4 + 1], R.oacc[ddb][4 * r4 + 2], R.oacc[ddb][4 * r4 + 3]);
             }
+        // (a wave's LDS operations complete in order: its reads below see its writes above; no other wave touches them)
+        float *dst = part_o + prow0 * kD;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row_i = 2 * i + half, c = lane & 31;
+            const float4 x = *(const float4 *)(stage + row_i * (kD * 4) + ((c ^ row_i) << 4));
+            *(float4 *)(dst + row_i * kD + 4 * c) = x;
+        }
     }
 }
 
