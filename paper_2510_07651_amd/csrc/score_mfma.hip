@@ -60,6 +60,7 @@ struct Sweep1Regs {
     f32x16 oacc[4];       // O^T accumulators: head_dim block x 16 registers
     f32x16 s_cur;         // raw q.k of the block whose softmax is due
     PiecePair phi[2], plo[2];   // two-piece softmax weights of the previous block, per k-step
+    float p[16];          // the same weights in fp32, from the step that formed them to the step that packs them
     float m_ref, m_true;  // reference of the running sums (raw q.k units, see kLazyRescale); true running max
     float lsum;           // this lane's share of the running sum
     float alpha;          // rescale of oacc still owed from the previous step (1 = none)
@@ -113,6 +114,20 @@ __device__ __forceinline__ void add_back(Sweep1Regs &R, const char *vh, int tok,
     add_back_apply(R, x, val, ref_l, ref_o, half);
 }
 
+// P = hi + lo for the matrix cores: hi keeps the top 16 bits of the fp32 weight (a bf16 by truncation), lo is the
+// exact remainder rounded to bf16.
+__device__ __forceinline__ void pack_weights(Sweep1Regs &R) {
+#pragma unroll
+    for (int sx = 0; sx < 2; ++sx)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float p0 = R.p[8 * sx + 2 * e], p1 = R.p[8 * sx + 2 * e + 1];
+            const uint32_t h0 = __float_as_uint(p0) & 0xffff0000u, h1 = __float_as_uint(p1) & 0xffff0000u;
+            R.phi[sx].u[e] = __builtin_amdgcn_perm(h1, h0, 0x07060302u);     // {h0 >> 16, h1 >> 16}
+            R.plo[sx].u[e] = pack_bf16(p0 - __uint_as_float(h0), p1 - __uint_as_float(h1));
+        }
+}
+
 // One pipeline step n of sweep 1 (PH = n mod 4 fixes every LDS slot at compile time):
 //   matrix cores: O^T += V^T P^T of block n-1, S^T = K Q^T of block n+1
 //   vector ALUs : online softmax of block n
@@ -162,6 +177,23 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
     for (int kk = 0; kk < 8; ++kk) {
         const bf16x8 a = kNeedO ? ka[kk] : lds_read16(smem + kKBase + koff[kk]);
         s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, R.q[kk], s_next, 0, 0, 0);
+    }
+    // ---- vector ALUs: block n-1's weights into operand form, in the shadow of the chain above (the second part of
+    // the step, whose matrix ops they feed, has the exponentials of block n for company) ----
+    if (kNeedO) {
+        pack_weights(R);
+#pragma unroll
+        for (int sx = 0; sx < 2; ++sx)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {       // (pinned here: left alone, the packing sinks into the step's second part)
+                asm volatile("" : "+v"(R.phi[sx].u[e]));
+                asm volatile("" : "+v"(R.plo[sx].u[e]));
+            }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {           // one matrix op, then its share of the packing
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 7, 0);
+        }
     }
     // ---- vector ALUs: block n ----
     f32x16 s = R.s_cur;
@@ -248,31 +280,29 @@ __device__ __forceinline__ void sweep1_step(Sweep1Regs &R, const char *smem, uin
         mref = m_new == -INFINITY ? 0.f : mref;
     }
     R.m_ref = m_new;
-    float p[16], psum = 0.f;
+    float psum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-        p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -mref));
-        psum += p[r];
+        R.p[r] = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -mref));
+        psum += R.p[r];
     }
     R.lsum = fmaf(R.lsum, alpha, psum);
     if (kNeedO) {
-        // P = hi + lo: hi keeps the top 16 bits of the fp32 weight (a bf16 by truncation),
-        // lo is the exact remainder rounded to bf16.
-#pragma unroll
-        for (int sx = 0; sx < 2; ++sx)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float p0 = p[8 * sx + 2 * e], p1 = p[8 * sx + 2 * e + 1];
-                const uint32_t h0 = __float_as_uint(p0) & 0xffff0000u, h1 = __float_as_uint(p1) & 0xffff0000u;
-                R.phi[sx].u[e] = __builtin_amdgcn_perm(h1, h0, 0x07060302u);     // {h0 >> 16, h1 >> 16}
-                R.plo[sx].u[e] = pack_bf16(p0 - __uint_as_float(h0), p1 - __uint_as_float(h1));
-            }
         R.alpha = alpha;
         R.rescale = __any(moved);      // uniform and rare once the running max has settled
     }
     R.s_cur = s_next;
-    // (the two-part step is left to the compiler's own schedule: it measured faster that way)
-    if (!kNeedO) interleave_hint<8, 12, 1>();
+    if (kNeedO) {
+        // second part: the remaining value operands first, then one matrix op per three vector ops (the exponentials go along)
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+        }
+    } else {
+        interleave_hint<8, 12, 1>();
+    }
 }
 
 // Grid: x = sequence split, y = 128-row chunk, z = (b, KV head).
@@ -336,6 +366,8 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
     for (int sx = 0; sx < 2; ++sx)
 #pragma unroll
         for (int e = 0; e < 4; ++e) { R.phi[sx].u[e] = 0; R.plo[sx].u[e] = 0; }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) R.p[r] = 0.f;
     R.m_ref = -INFINITY;
     R.m_true = -INFINITY;
     R.lsum = 0.f;
@@ -412,6 +444,7 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
     }
     wait_async_loads();        // the blocks fetched past the end must have landed before the LDS is given back
     if (kNeedO && wave_active) {      // drain: P V of the last block (n_total - 1, in slot 3 of the V ring)
+        pack_weights(R);
         if (R.rescale) {
 #pragma unroll
             for (int i = 0; i < 4; ++i)
