@@ -10,6 +10,7 @@ namespace mfma {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short i16x4;
 typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __bf16 bf16_2 __attribute__((ext_vector_type(2)));
@@ -48,16 +49,17 @@ __device__ __forceinline__ uint32_t lds_offset_of(const void *p) {
 
 // One direct-to-LDS transfer: every lane supplies the address of 16 bytes in global
 // memory; the wave's 1 KB lands contiguously at LDS byte `lds_off` (lane l at +16 l).
+// Marked non-temporal: every sweep reads K and V once, and they are far larger than the L2.
 // Issued from inline assembly so that the compiler's wait-count bookkeeping does not tie
 // later LDS reads of OTHER tiles to these transfers; the kernels wait for them
 // explicitly (wait_async_loads + barrier) before the tile is read.
 __device__ __forceinline__ void dma16(const void *gptr, uint32_t lds_off) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_off), "v"(gptr) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" ::"s"(lds_off), "v"(gptr) : "memory");
 }
 // Same transfer with the address split into a wave-uniform 64-bit base (scalar registers)
 // and a per-lane 32-bit byte offset: no vector-ALU address arithmetic per transfer.
 __device__ __forceinline__ void dma16_based(const void *sbase, uint32_t voff, uint32_t lds_off) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_off), "v"(voff), "s"(sbase) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt" ::"s"(lds_off), "v"(voff), "s"(sbase) : "memory");
 }
 __device__ __forceinline__ void wait_async_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 // Asynchronous copy of one 64-row tile.  Each wave issues four transfers; lane l of

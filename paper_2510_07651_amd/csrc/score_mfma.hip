@@ -494,8 +494,10 @@ __global__ __launch_bounds__(kThreads, 2) void mfma_sweep1(const uint16_t *__res
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
             const int row_i = 2 * i + half, c = lane & 31;
-            const float4 x = *(const float4 *)(stage + row_i * (kD * 4) + ((c ^ row_i) << 4));
-            *(float4 *)(dst + row_i * kD + 4 * c) = x;
+            const f32x4 x = *(const f32x4 *)(stage + row_i * (kD * 4) + ((c ^ row_i) << 4));
+            // (streaming store: the partials are read once, by the combine step, and 35 MB of them kept dirty in the
+            // L2 would all be written back when the kernel ends)
+            __builtin_nontemporal_store(x, (f32x4 *)(dst + row_i * kD + 4 * c));
         }
     }
 }

@@ -33,7 +33,6 @@ namespace obc {
 using namespace mfma;
 namespace {
 
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 typedef const __attribute__((address_space(3))) char *lds_ptr;
 
 constexpr int kSlots = 4;                       // tiles in the ring
