@@ -36,10 +36,12 @@ constexpr int kItems = 4;                              // consecutive scores per
 constexpr int kChunk = kSelThreads * kItems;           // 4096 scores per chunk
 
 // Monotone map float -> uint32: larger float <=> larger key.  -0.0 is folded onto +0.0,
-// every NaN maps to 0 (below -inf).
+// every NaN maps to 1 (below -inf, whose key is 0x007fffff).  No score maps to 0: that key marks
+// positions that do not exist (past a sequence's length), which therefore rank below every token
+// and never reach a threshold as long as the budget does not exceed the length.
 __device__ __forceinline__ uint32_t order_key(float f) {
     uint32_t u = __float_as_uint(f);
-    if (f != f) return 0u;
+    if (f != f) return 1u;
     if (u == 0x80000000u) u = 0u;
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
@@ -65,6 +67,27 @@ __device__ __forceinline__ void histogram_add(int *hist, uint32_t digit, bool ac
     if (active) atomicAdd(&hist[digit], 1);
 }
 
+// Inclusive scan of one int per lane over the wave, register to register: four data-parallel-primitive steps inside
+// each row of 16 lanes (shifts by 1, 2, 4, 8, lanes outside the row reading zero), then the totals of the rows on the
+// far side, read from their end lanes.  kSuffix: lane l gets the sum over lanes >= l; otherwise over lanes <= l.
+template <bool kSuffix>
+__device__ __forceinline__ int wave_scan(int x, int lane) {
+    constexpr int kShift = kSuffix ? 0x100 : 0x110;        // row_shl : row_shr
+    x += __builtin_amdgcn_update_dpp(0, x, kShift + 1, 0xf, 0xf, true);
+    x += __builtin_amdgcn_update_dpp(0, x, kShift + 2, 0xf, 0xf, true);
+    x += __builtin_amdgcn_update_dpp(0, x, kShift + 4, 0xf, 0xf, true);
+    x += __builtin_amdgcn_update_dpp(0, x, kShift + 8, 0xf, 0xf, true);
+    const int row = lane >> 4;
+    if (kSuffix) {
+        const int t1 = __builtin_amdgcn_readlane(x, 16), t2 = __builtin_amdgcn_readlane(x, 32), t3 = __builtin_amdgcn_readlane(x, 48);
+        x += row == 0 ? t1 + t2 + t3 : row == 1 ? t2 + t3 : row == 2 ? t3 : 0;
+    } else {
+        const int t0 = __builtin_amdgcn_readlane(x, 15), t1 = __builtin_amdgcn_readlane(x, 31), t2 = __builtin_amdgcn_readlane(x, 47);
+        x += row == 3 ? t0 + t1 + t2 : row == 2 ? t0 + t1 : row == 1 ? t0 : 0;
+    }
+    return x;
+}
+
 // After a histogram pass over `bins` bins: which digit holds the element of rank `remaining`
 // (from the top), and that element's rank inside the digit.  All threads get the same answer.
 __device__ __forceinline__ void pick_digit(SelectShared &sh, int remaining, uint32_t *digit, int *new_remaining) {
@@ -73,12 +96,7 @@ __device__ __forceinline__ void pick_digit(SelectShared &sh, int remaining, uint
     // thread t owns digits 2t (lo) and 2t+1 (hi); suffix sums over threads t' > t
     const int lo = sh.hist[2 * tid], hi = sh.hist[2 * tid + 1];
     const int mine = lo + hi;
-    int incl = mine;                    // inclusive suffix scan inside the wave (towards higher lanes)
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int t = __shfl_down(incl, off);
-        if (lane + off < 64) incl += t;
-    }
+    const int incl = wave_scan<true>(mine, lane);          // inclusive suffix scan inside the wave (towards higher lanes)
     if (lane == 0) sh.wave_tot[wave] = incl;
     __syncthreads();
     int above = incl - mine;            // elements in digits of higher threads
@@ -113,12 +131,7 @@ __device__ __forceinline__ void emit_chunk(SelectShared &sh, const uint32_t (&ke
         eq[e] = i0 + e < len && key[e] == thr;
         packed += (gt[e] ? 0x10000 : 0) + (eq[e] ? 1 : 0);
     }
-    int incl = packed;                  // inclusive scan inside the wave
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int t = __shfl_up(incl, off);
-        if (lane >= off) incl += t;
-    }
+    const int incl = wave_scan<false>(packed, lane);       // inclusive scan inside the wave
     if (lane == 63) sh.wave_tot[wave] = incl;
     __syncthreads();
     int before = incl - packed, total = 0;
@@ -155,12 +168,11 @@ __device__ __forceinline__ void emit_resident(SelectShared &sh, const uint32_t (
 #pragma unroll
     for (int c = 0; c < kRegChunks; ++c) {
         // Counts over the lower lanes and over the wave from the lane masks of the comparisons (no shuffles).
-        const int i0 = c * kChunk + tid * kItems;
         int gt_lower = 0, eq_lower = 0, gt_wave = 0, eq_wave = 0;
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
-            const bool in = c < n_chunks && i0 + e < len;
-            const unsigned long long mg = __ballot(in && keys[c][e] > thr), me = __ballot(in && keys[c][e] == thr);
+            // (no range checks: positions past the length and chunks past the head hold key 0 < thr)
+            const unsigned long long mg = __ballot(keys[c][e] > thr), me = __ballot(keys[c][e] == thr);
             gt_lower += __builtin_amdgcn_mbcnt_hi((uint32_t)(mg >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mg, 0));
             eq_lower += __builtin_amdgcn_mbcnt_hi((uint32_t)(me >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)me, 0));
             gt_wave += __popcll(mg);
@@ -182,12 +194,7 @@ __device__ __forceinline__ void emit_resident(SelectShared &sh, const uint32_t (
             gt[u] = t >> 16; eq[u] = t & 0xffff;
             gsum += gt[u]; esum += eq[u];
         }
-        int ginc = gsum, einc = esum;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int tg = __shfl_up(ginc, off), te = __shfl_up(einc, off);
-            if (lane >= off) { ginc += tg; einc += te; }
-        }
+        const int ginc = wave_scan<false>(gsum, lane), einc = wave_scan<false>(esum, lane);
         int g = ginc - gsum, q = einc - esum;       // exclusive
 #pragma unroll
         for (int u = 0; u < kPer; ++u) {
@@ -208,8 +215,7 @@ __device__ __forceinline__ void emit_resident(SelectShared &sh, const uint32_t (
         int eq_before = sh.cw_eq[c * kSelWaves + wave] + (before[c] & 0xffff);
 #pragma unroll
         for (int e = 0; e < kItems; ++e) {
-            const bool in = i0 + e < len;
-            const bool gt = in && keys[c][e] > thr_again, eq = in && keys[c][e] == thr_again;
+            const bool gt = keys[c][e] > thr_again, eq = keys[c][e] == thr_again;
             if (gt || (eq && eq_before < need_eq)) {
                 const int pos = gt_before + min(eq_before, need_eq);
                 if (pos < budget) out[pos] = i0 + e;          // always true; guards the store
@@ -220,11 +226,103 @@ __device__ __forceinline__ void emit_resident(SelectShared &sh, const uint32_t (
     }
 }
 
+// The same when every key equal to the threshold is kept (no tie is cut: the usual case): a key is kept iff it is
+// >= the threshold, so one comparison and one count per key do.
+template <int kRegChunks>
+__device__ __forceinline__ void emit_resident_uncut(SelectShared &sh, const uint32_t (&keys)[kRegChunks][kItems],
+                                                    int n_chunks, uint32_t thr, int budget, int32_t *out) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    int before[kRegChunks];                     // kept keys of the wave's lower lanes in chunk c
+#pragma unroll
+    for (int c = 0; c < kRegChunks; ++c) {
+        int lower = 0, in_wave = 0;
+#pragma unroll
+        for (int e = 0; e < kItems; ++e) {
+            const unsigned long long m = __ballot(keys[c][e] >= thr);
+            lower += __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
+            in_wave += __popcll(m);
+        }
+        if (lane == 0) sh.cw_tot[c * kSelWaves + wave] = in_wave;
+        before[c] = lower;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        constexpr int kPer = kRegChunks * kSelWaves / 64 > 0 ? kRegChunks * kSelWaves / 64 : 1;
+        constexpr int kEntries = kRegChunks * kSelWaves;
+        int n[kPer], sum = 0;
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int j = lane * kPer + u;
+            n[u] = j < kEntries ? sh.cw_tot[j] : 0;
+            sum += n[u];
+        }
+        int g = wave_scan<false>(sum, lane) - sum;  // exclusive
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+            const int j = lane * kPer + u;
+            if (j < kEntries) sh.cw_gt[j] = g;
+            g += n[u];
+        }
+    }
+    __syncthreads();
+    uint32_t thr_again = thr;                       // (compared again rather than kept: the lane masks would not fit)
+    asm volatile("" : "+v"(thr_again));
+#pragma unroll
+    for (int c = 0; c < kRegChunks; ++c) {
+        if (c >= n_chunks) continue;                // uniform
+        const int i0 = c * kChunk + tid * kItems;
+        int pos = sh.cw_gt[c * kSelWaves + wave] + before[c];
+#pragma unroll
+        for (int e = 0; e < kItems; ++e) {
+            const bool keep = keys[c][e] >= thr_again;
+            if (keep && pos < budget) out[pos] = i0 + e;      // (pos < budget always holds; it guards the store)
+            pos += keep ? 1 : 0;
+        }
+    }
+}
+
 // Keys of chunks c0 .. c0 + kRegChunks - 1 of one head (128-bit loads where possible).
 template <int kRegChunks>
 __device__ __forceinline__ void load_batch(uint32_t (&keys)[kRegChunks][kItems], const float *__restrict__ s, int c0,
                                            int n_chunks, int len, bool vec_ok, int first, int cutoff, int radius,
                                            bool keys_in = false) {
+    if (radius == 0 && !keys_in && vec_ok) {              // uniform: plain scores of an aligned head, the usual case
+        // Every load of the batch goes out before any key is formed: one memory round trip, not one per chunk.
+        float4 f[kRegChunks];
+#pragma unroll
+        for (int c = 0; c < kRegChunks; ++c) {
+            const int i0 = (c0 + c) * kChunk + (int)threadIdx.x * kItems;
+            f[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (c0 + c < n_chunks) {                      // uniform
+                if (i0 + kItems <= len) {
+                    f[c] = *(const float4 *)(s + i0);
+                } else {                                  // the head's last, partial group of four
+                    if (i0 < len) f[c].x = s[i0];
+                    if (i0 + 1 < len) f[c].y = s[i0 + 1];
+                    if (i0 + 2 < len) f[c].z = s[i0 + 2];
+                }
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < kRegChunks; ++c) {
+            if (c0 + c < n_chunks) {                      // uniform
+                const int i0 = (c0 + c) * kChunk + (int)threadIdx.x * kItems;
+                keys[c][0] = order_key(f[c].x); keys[c][1] = order_key(f[c].y);
+                keys[c][2] = order_key(f[c].z); keys[c][3] = order_key(f[c].w);
+                if (i0 + kItems > len) {                  // positions past the length
+#pragma unroll
+                    for (int e = 0; e < kItems; ++e)
+                        if (i0 + e >= len) keys[c][e] = 0u;
+                }
+                if (i0 < first || i0 + kItems > cutoff) { // some of these tokens are protected
+#pragma unroll
+                    for (int e = 0; e < kItems; ++e)
+                        if (i0 + e < first || (i0 + e >= cutoff && i0 + e < len)) keys[c][e] = 0xffffffffu;
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int c = 0; c < kRegChunks; ++c) {
         if (c0 + c < n_chunks) {                          // uniform
@@ -300,14 +398,13 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
         sh.hist[2 * tid + 1] = 0;
         __syncthreads();
         if constexpr (kResident) {
+            // (positions past the length hold key 0: they land in the lowest class and are never reached)
 #pragma unroll
             for (int c = 0; c < kRegChunks; ++c) {
                 if (c < n_chunks) {                       // uniform
 #pragma unroll
-                    for (int e = 0; e < kItems; ++e) {
-                        const bool in = c * kChunk + tid * kItems + e < len;
-                        histogram_add(sh.hist, (keys[c][e] >> shift) & dmask, in && ((keys[c][e] & mask) == prefix));
-                    }
+                    for (int e = 0; e < kItems; ++e)
+                        if ((keys[c][e] & mask) == prefix) atomicAdd(&sh.hist[(keys[c][e] >> shift) & dmask], 1);
                 }
             }
         } else {
@@ -336,7 +433,9 @@ __global__ __launch_bounds__(kSelThreads) void select_topk(const float *__restri
     // ---- ordered sweep ----
     int gt_base = 0, eq_base = 0;
     if constexpr (kResident) {
-        emit_resident<kRegChunks>(sh, keys, n_chunks, len, thr, need_eq, budget, out);
+        // (the last pass's counters are still in place: the threshold's own counter is the number of keys equal to it)
+        if (need_eq == sh.hist[thr & 1023u]) emit_resident_uncut<kRegChunks>(sh, keys, n_chunks, thr, budget, out);
+        else emit_resident<kRegChunks>(sh, keys, n_chunks, len, thr, need_eq, budget, out);
     } else {
         for (int c0 = 0; c0 < n_chunks; c0 += kRegChunks) {
             load_batch<kRegChunks>(keys, s, c0, n_chunks, len, vec_ok, first, cutoff, radius, keys_in != 0);
