@@ -725,7 +725,11 @@ hipError_t launch_select(const float *scores, int budget, int32_t *keep_idx, int
         return launch_select_sliced(scores, budget, keep_idx, B, Hkv, N, ragged, lens, first, tail, radius, keys_in,
                                     workspace, stream);
     const dim3 grid(B * Hkv), block(kSelThreads);
-    if (N <= 8 * kChunk)
+    if (N <= kChunk)             // (short heads: fewer unrolled chunk bodies to step through)
+        select_topk<1, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, radius, keys_in, keep_idx);
+    else if (N <= 2 * kChunk)
+        select_topk<2, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, radius, keys_in, keep_idx);
+    else if (N <= 8 * kChunk)
         select_topk<8, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, radius, keys_in, keep_idx);
     else if (N <= 16 * kChunk)
         select_topk<16, true><<<grid, block, 0, stream>>>(scores, N, budget, Hkv, ragged, lens, first, tail, radius, keys_in, keep_idx);
