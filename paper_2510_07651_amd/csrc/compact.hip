@@ -23,7 +23,11 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4 *__restrict__ k, 
     p = p >= N ? N - 1 : p;
     const size_t src = (bg * N + p) * row_vec + c;
     const uint4 *in = blockIdx.y == 0 ? k : v;
-    out[t] = in[src];
+    // (streaming store: the compacted rows are not read again by this path, and kept dirty in the L2 they would be
+    // written back in one burst when the kernel ends)
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 x = *(const u32x4 *)(in + src);
+    __builtin_nontemporal_store(x, (u32x4 *)(out + t));
 }
 
 // Running scores follow their tokens through an eviction: out[bg, j] = in[bg, keep[bg, j]] for
