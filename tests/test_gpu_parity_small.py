@@ -456,19 +456,22 @@ def test_compact_inplace_matches_oracle_gather(dtype, d, N):
     np.testing.assert_array_equal(sd.cpu().numpy()[:, :, :25], s.numpy()[:, :, 5:30])
 
 
-@pytest.mark.parametrize("variant", ["key", "value", "joint"])
-def test_decode_step_on_a_ragged_batch_with_ties(variant):
+@pytest.mark.parametrize("variant,Hq,Hkv,d,dtype", [("key", 8, 2, 128, torch.bfloat16), ("value", 8, 2, 128, torch.bfloat16),
+                                                    ("joint", 8, 2, 128, torch.bfloat16), ("joint", 7, 1, 128, torch.bfloat16),
+                                                    ("joint", 4, 2, 64, torch.bfloat16), ("joint", 4, 2, 64, torch.float32),
+                                                    ("attn", 8, 2, 128, torch.bfloat16)])
+def test_decode_step_on_a_ragged_batch_with_ties(variant, Hq, Hkv, d, dtype):
     """obc_decode_step on sequences of different lengths, one of them with every candidate tied (zero query, equal
     value rows: Eq. 4-6 then give every token the same score): the accumulated scores equal obc_score's own, the
     dropped position is the oracle's choice on those fp32 scores (lowest score, the later position among equals, sinks
     and the recent window exempt), and K, V and scores close the gap exactly."""
-    B, Hq, Hkv, d, N = 3, 8, 2, 128, 200
+    B, N = 3, 200
     sinks, recent = 4, 16
     lens = [200, 77, 131]
     g = torch.Generator().manual_seed(97)
-    q = torch.randn(B, Hq, 1, d, generator=g).to(torch.bfloat16)
-    k = torch.randn(B, Hkv, N, d, generator=g).to(torch.bfloat16)
-    v = torch.randn(B, Hkv, N, d, generator=g).to(torch.bfloat16)
+    q = torch.randn(B, Hq, 1, d, generator=g).to(dtype)
+    k = torch.randn(B, Hkv, N, d, generator=g).to(dtype)
+    v = torch.randn(B, Hkv, N, d, generator=g).to(dtype)
     run = torch.rand(B, Hkv, N, generator=g) * 0.01
     q[1] = 0; v[1] = v[1, :, :1]; run[1] = 0.25                       # sequence 1: all tied
     for b, L in enumerate(lens):
