@@ -106,7 +106,7 @@ using namespace obc;
 
 extern "C" {
 
-int obc_version(void) { return 103; }
+int obc_version(void) { return 104; }
 
 int obc_init(void) {
     void *p = nullptr;
