@@ -20,11 +20,14 @@
 // wave: while the vector ALUs turn block n's accumulators into softmax weights, the matrix
 // cores already work on block n+1's K Q^T and on block n-1's P V product; the streams of
 // one step are independent, sit in one basic block, and the instruction scheduler
-// interleaves them.  Sweep 2 runs a block's matrix phase and vector phase back to back and
-// leaves the overlap to the second wave on the SIMD (its stationary operands and row
-// constants leave no registers for a second set of accumulators).  K and V travel HBM -> LDS
-// with direct-to-LDS loads: in sweep 1 as 32-token blocks through four-slot rings, three
-// batches in flight; in sweep 2 as 64-token tiles, double-buffered.
+// interleaves them.  Sweep 2 exists in two forms.  The one in this file gives a wave 32 rows, runs
+// a block's matrix phase and vector phase back to back and leaves the overlap to the second wave
+// on the SIMD (its stationary operands and row constants leave no registers for a second set of
+// accumulators).  The register-blocked form (score_mfma_wide.hip: 64 rows per wave, stationary
+// operands in the accumulator file, the wave pipelined against itself) serves the key, joint and
+// all-three variants whenever every 128-row chunk is at least three quarters full.  K and V travel
+// HBM -> LDS with direct-to-LDS loads: in sweep 1 as 32-token blocks through four-slot rings, three
+// batches in flight; in sweep 2 as 64-token tiles, double-buffered here, a four-slot ring there.
 //
 // Precision.  The matrix cores take bf16 operands, and rows whose attention is
 // concentrated on a few keys are sensitive to that rounding (the scores of those keys
