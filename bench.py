@@ -355,20 +355,21 @@ def main():
             m = re.search(r"obc_score \(all mfma_\* kernels\):.*?=\s*(\d+) bytes per call", f.read())
         traffic = int(m.group(1)) if m else None
         traffic_source = "profiles/" + os.path.basename(tpath) if m else None
-    # Vector-ALU load of the two sweeps beside the memory roofline: per (window row, token) pair the kernels issue ~21
-    # fp32 lane-operations (exp2 counted as 4: quarter rate) and the matrix ops take the vector issue port for another
-    # ~9 lane-operations' worth; the chip issues 256 CUs x 4 SIMDs x 16 lanes per clock at 2.4 GHz (no packed fp32).
+    # Vector-ALU load of the two sweeps beside the memory roofline: the two kernels issue ~22.5 vector instructions per
+    # lane and (window row, token) pair, matrix ops included as one each (hardware counter SQ_INSTS_VALU of the two
+    # sweeps over the pair count, profiles/sq_counters_c3_*.txt); the chip's published fp32 vector peak, 157.3 TFLOP/s,
+    # is 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz fused multiply-adds, i.e. 7.86e13 lane-operations per second.
     pairs = Hq * W * tokens
-    valu_rate = 256 * 4 * 16 * 2.4e9
-    valu_ms = pairs * (21 + 9) / valu_rate * 1e3
+    lane_ops_per_pair = 22.5
+    valu_rate = 256 * 4 * 32 * 2.4e9
+    valu_ms = pairs * lane_ops_per_pair / valu_rate * 1e3
     roofline = {
         "bound": "hbm", "kernel": "obc_score = mfma_sweep1 + mfma_combine + mfma_sweep2",
         "achieved": round(achieved, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
         "frac": round(achieved / PEAK_HBM_GBPS, 4), "traffic": traffic, "traffic_source": traffic_source,
         "algorithmic_bytes": algo_bytes,
-        "valu": {"pairs": pairs, "lane_ops_per_pair": 21, "mfma_issue_lane_ops_per_pair": 9,
-                 "peak_lane_ops_per_s": valu_rate, "ms_at_peak": round(valu_ms, 4),
-                 "frac": round(valu_ms / ms["obc_score"], 4)},
+        "valu": {"pairs": pairs, "lane_ops_per_pair": lane_ops_per_pair, "peak_lane_ops_per_s": valu_rate,
+                 "ms_at_peak": round(valu_ms, 4), "frac": round(valu_ms / ms["obc_score"], 4)},
         "kernel_ms": {k: round(v, 4) for k, v in ms.items()},
         # plain streaming read of the same K and V buffers on this machine: the practical ceiling
         "stream_read_GBps": round(2 * sets[0]["k"].numel() * esize / (ms_stream * 1e-3) / 1e9, 1),
